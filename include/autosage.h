@@ -1,0 +1,233 @@
+/*
+ * autosage.h -- C ABI of the MI355X (gfx950) CSR SpMM / SDDMM / CSR-attention library.
+ *
+ * Operations (paper: "Notation", "Preliminaries", "Method: Kernel templates",
+ * "Scheduler: estimate -> micro-probe -> guardrail", the decision sketch, Proposition 1):
+ *
+ *   SpMM            C = A B,  A sparse CSR (rowptr, colind, val), B dense
+ *   SDDMM           out[p] = <X_i, Y_j> for every stored (i, j) of A, in CSR order
+ *   row-softmax     numerically stable softmax over the stored entries of each row
+ *   CSR attention   SDDMM -> row-softmax -> SpMM on one sparsity pattern, multi-head
+ *   selector        estimate from the degree histogram -> timed probes on a row sample
+ *                   -> guardrail (accept iff t* <= alpha * t_baseline) -> persistent cache
+ *
+ * Conventions that hold for every entry point unless its comment says otherwise
+ *   - "dev" pointers are device (HBM) pointers owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library never frees or keeps a caller pointer.
+ *   - Indices are int32.  Dense operands are row-major with the feature index minor and a
+ *     leading dimension (in elements) >= the feature count.
+ *   - Dense INPUT operands have dtype `dt` (fp32 or bf16 bit patterns); val, scores and all
+ *     outputs are fp32; accumulation is fp32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls with an
+ *     explicit schedule only enqueue work and never synchronise.  Calls with sched == NULL
+ *     consult the selector, which synchronises the stream only when it has to probe.
+ *   - `workspace` is caller-provided device scratch of at least autosage_workspace_bytes()
+ *     bytes, 256-byte aligned; it may be NULL when the schedule needs none (no hub split and
+ *     a non-fused attention is never the case: attention always needs it).
+ *   - Every function returns an autosage_status_t; nothing throws or aborts across the ABI.
+ *     Arguments are checked before anything is launched.
+ *   - Outputs must not alias inputs (row-softmax may run in place).
+ *   - For a fixed schedule the result is bit-reproducible: no floating-point atomics are used.
+ */
+#ifndef AUTOSAGE_H
+#define AUTOSAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct autosage_ctx* autosage_handle_t;
+
+typedef enum {
+    AUTOSAGE_OK = 0,
+    AUTOSAGE_ERR_INVALID_ARG = 1,
+    AUTOSAGE_ERR_UNSUPPORTED = 2,
+    AUTOSAGE_ERR_WORKSPACE_TOO_SMALL = 3,
+    AUTOSAGE_ERR_HIP = 4,
+    AUTOSAGE_ERR_IO = 5,
+    AUTOSAGE_ERR_REPLAY_MISS = 6
+} autosage_status_t;
+
+typedef enum { AUTOSAGE_F32 = 0, AUTOSAGE_BF16 = 1 } autosage_dtype_t;
+
+typedef enum {
+    AUTOSAGE_OP_SPMM = 0,
+    AUTOSAGE_OP_SDDMM = 1,
+    AUTOSAGE_OP_SOFTMAX = 2,
+    AUTOSAGE_OP_ATTENTION = 3
+} autosage_op_t;
+
+/* Row mappings (the paper's kernel-variant table, re-cut for 64-wide wavefronts). */
+typedef enum {
+    AUTOSAGE_MAP_PLAIN = 0,      /* fallback: one wavefront per row, one lane per feature, 4-byte loads */
+    AUTOSAGE_MAP_WAVE_ROW = 1,   /* one wavefront per row; lane groups split the row's nonzeros */
+    AUTOSAGE_MAP_MULTI_ROW = 2   /* several rows per wavefront: every lane group owns one row */
+} autosage_mapping_t;
+
+/* A schedule = one point of the knob space (feature tile, mapping, vector width, hub split). */
+typedef struct {
+    int32_t mapping;       /* autosage_mapping_t */
+    int32_t f_tile;        /* features one wavefront covers per pass; 0 = smallest tile covering F (max 2048 B per lane group pass) */
+    int32_t waves_per_wg;  /* wavefronts per workgroup: 1, 2, 4, 8 or 16; 0 = 4 */
+    int32_t vec_bytes;     /* bytes per lane load: 4, 8 or 16; 0 = widest legal for F, ld and pointer alignment */
+    int32_t unroll;        /* nonzeros in flight per lane group: 1, 2, 4 or 8; 0 = library default */
+    int32_t hub_t;         /* rows with degree >= hub_t are split over workgroups; 0 = no hub split */
+    int32_t hub_chunk;     /* nonzeros per hub chunk; 0 = hub_t */
+    int32_t xcd_remap;     /* 1 = consecutive row blocks stay on one XCD (contiguous row range per L2) */
+} autosage_schedule_t;
+
+/* ---- lifetime -------------------------------------------------------------------------- */
+
+/* Creates a handle bound to HIP device `device_id` and reads the AUTOSAGE_* environment
+ * toggles once (AUTOSAGE_FTILE, AUTOSAGE_WPB, AUTOSAGE_HUB_T, AUTOSAGE_PROBE_FRAC,
+ * AUTOSAGE_PROBE_ITERS, AUTOSAGE_PROBE_CAP_MS, AUTOSAGE_PROBE_TOPK, AUTOSAGE_PROBE_MIN_ROWS,
+ * AUTOSAGE_ALPHA, AUTOSAGE_CACHE (file loaded now and saved by autosage_destroy),
+ * AUTOSAGE_REPLAY_ONLY); the paper's Implementation section names them.
+ * device_id < 0 creates a host-only handle: selector, cache and estimate functions work,
+ * every compute call returns AUTOSAGE_ERR_UNSUPPORTED. */
+autosage_status_t autosage_create(autosage_handle_t* out, int device_id);
+autosage_status_t autosage_destroy(autosage_handle_t h);
+const char* autosage_status_string(autosage_status_t s);
+
+/* Sets a selector parameter by name: "alpha", "probe_frac", "probe_iters", "probe_cap_ms",
+ * "probe_topk", "probe_min_rows", "replay_only", "confirm_full", "memoize_signature".
+ * Unknown name -> AUTOSAGE_ERR_INVALID_ARG. */
+autosage_status_t autosage_set_param(autosage_handle_t h, const char* name, double value);
+autosage_status_t autosage_get_param(autosage_handle_t h, const char* name, double* value);
+
+/* ---- the hot path ---------------------------------------------------------------------- */
+
+/* SpMM (Notation: C = A B).  C[n_rows, F] (fp32, dev) = A[n_rows, n_cols] * B[n_cols, F] (dt, dev).
+ * rowptr[n_rows+1], colind[nnz], val[nnz] are dev pointers.  Empty rows give zero rows.
+ * sched == NULL: the selector chooses (cache -> probe -> guardrail); else the given schedule runs.
+ * Errors: INVALID_ARG (null pointer, F <= 0, ld < F, nnz >= 2^31, bad schedule field),
+ * UNSUPPORTED (vec_bytes illegal for this F / alignment), WORKSPACE_TOO_SMALL, HIP. */
+autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                const int32_t* rowptr, const int32_t* colind, const float* val,
+                                const void* B, int64_t ldb, float* C, int64_t ldc, int32_t F,
+                                autosage_dtype_t dt, const autosage_schedule_t* sched,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* SDDMM (Notation: A~_ij = <X_i, Y_j> on the pattern of A).  out[p] (fp32, dev, CSR order) for
+ * every stored p of row i; X is [n_rows, F], Y is [n_cols, F] (dt, dev).  val is not read
+ * (pattern only) and may be NULL.  Same schedule / error rules as autosage_spmm. */
+autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                 const int32_t* rowptr, const int32_t* colind, const float* val,
+                                 const void* X, int64_t ldx, const void* Y, int64_t ldy, int32_t F,
+                                 autosage_dtype_t dt, float* out, const autosage_schedule_t* sched,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Row-softmax (Kernel templates: numerically stable CSR row-softmax).  in/out are [nnz, H] fp32
+ * dev arrays (head index minor); for each row and head: m = max, e = exp(s - m), out = e / sum e.
+ * Rows without nonzeros write nothing.  out may equal in.  hub_t > 0 splits rows of degree
+ * >= hub_t into chunks of hub_chunk (0 = hub_t) entries with a two-pass combine (needs workspace). */
+autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64_t n_rows, int64_t nnz,
+                                           const int32_t* rowptr, const float* in, float* out,
+                                           int32_t H, int32_t hub_t, int32_t hub_chunk,
+                                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* CSR attention (Preliminaries: SDDMM -> row-softmax -> SpMM).  Q, K, V are [N, H, d] (in_dt, dev,
+ * d minor), O is [N, H, d] fp32 dev.  S[p,h] = scale * <Q[i,h,:], K[j,h,:]>, P = row-softmax(S)
+ * per (row, head), O[i,h,:] = sum_p P[p,h] V[colind[p],h,:].  Rows without nonzeros give O = 0.
+ * val is ignored and may be NULL.  The [nnz, H] score array lives in the workspace.
+ * sched may be NULL (library default: hub split at 1024) or give hub_t / hub_chunk / waves_per_wg /
+ * unroll for all three stages; mapping, f_tile and vec_bytes are chosen from H and d. */
+autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t N, int64_t nnz,
+                                         const int32_t* rowptr, const int32_t* colind, const float* val,
+                                         const void* Q, const void* K, const void* V, float* O,
+                                         int32_t H, int32_t d, float scale, autosage_dtype_t in_dt,
+                                         const autosage_schedule_t* sched,
+                                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Workspace size in bytes (host only, no GPU work).  With sched != NULL: what that schedule needs
+ * (0 hub split -> a 256-byte minimum).  With sched == NULL: an upper bound over every schedule the
+ * selector may choose (hub thresholds >= 512), which is what calls with sched == NULL require.
+ * For SPMM / SDDMM pass the feature count in F and H = 1; for SOFTMAX pass H (F ignored, pass 1);
+ * for ATTENTION pass H and F = d (the bound includes the [nnz, H] fp32 score array). */
+autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autosage_op_t op, int64_t n_rows,
+                                           int64_t nnz, int32_t F, int32_t H,
+                                           const autosage_schedule_t* sched, size_t* bytes);
+
+/* ---- plan / index metadata (exposed so that it can be compared bit-exactly) ------------- */
+
+/* Heavy/light split (kernel-variant table: rows whose degree reaches the split threshold hubT).
+ *   hub_rows   (dev, capacity n_rows)     ascending { i : deg(i) >= hub_t }
+ *   chunk_ptr  (dev, capacity n_rows + 1) chunk_ptr[0] = 0, chunk_ptr[k+1] = chunk_ptr[k] + ceil(deg(hub_rows[k]) / hub_chunk)
+ *   light_rows (dev, capacity n_rows, may be NULL) ascending complement, empty rows included
+ * Chunk t of hub row r covers nonzeros [rowptr[r] + t*hub_chunk, min(rowptr[r] + (t+1)*hub_chunk, rowptr[r+1])).
+ * n_hub, n_light (host) are written after the stream has been synchronised.
+ * workspace: autosage_workspace_bytes(AUTOSAGE_OP_SPMM, ...) is always enough. */
+autosage_status_t autosage_hub_partition(autosage_handle_t h, int64_t n_rows, const int32_t* rowptr,
+                                         int32_t hub_t, int32_t hub_chunk,
+                                         int32_t* n_hub, int32_t* hub_rows, int32_t* chunk_ptr,
+                                         int32_t* n_light, int32_t* light_rows,
+                                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Degree features of the scheduler (feature extraction: rows, nnz, degree distribution).
+ * hist[0] = rows of degree 0; hist[b] = rows with 2^(b-1) <= deg < 2^b (host, 33 entries).
+ * signature = 64-bit FNV-1a over the little-endian int64 stream n_rows, n_cols, nnz, max_deg,
+ * hist[0..32], rowptr[floor(k * n_rows / 1023)] for k = 0..1023.  Synchronises the stream. */
+autosage_status_t autosage_graph_features(autosage_handle_t h, int64_t n_rows, int64_t n_cols,
+                                          const int32_t* rowptr, int64_t* hist33, int64_t* max_deg,
+                                          int64_t* nnz, uint64_t* signature, void* stream);
+
+/* Checks rowptr[0] == 0, monotone rowptr, rowptr[n_rows] == nnz and 0 <= colind < n_cols on the
+ * device; synchronises.  Returns AUTOSAGE_ERR_INVALID_ARG when the CSR arrays are inconsistent. */
+autosage_status_t autosage_validate_csr(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                        const int32_t* rowptr, const int32_t* colind, void* stream);
+
+/* ---- selector -------------------------------------------------------------------------- */
+
+/* Shortlist (Scheduler: "shortlist candidates with a roofline-style estimate").  Host only.
+ * From the degree histogram and the widths/alignments it ranks the legal schedules of `op` by an
+ * estimated time (seconds, ascending) and writes up to max_out of them.  align_bytes is the
+ * largest power of two (<= 16) dividing every dense base pointer and every ld * element size. */
+autosage_status_t autosage_shortlist(autosage_handle_t h, autosage_op_t op, int64_t n_rows, int64_t n_cols,
+                                     int64_t nnz, const int64_t* hist33, int64_t max_deg, int32_t F,
+                                     autosage_dtype_t dt, int32_t align_bytes,
+                                     autosage_schedule_t* out, double* est_seconds, int32_t max_out, int32_t* n_out);
+
+/* The decision rule of the decision sketch and Proposition 1, on given probe times (host only):
+ * best = first candidate with the strictly smallest time; accepted iff t_best <= alpha * t_baseline.
+ * Returns in *choice the accepted candidate's index or -1 for the baseline. */
+autosage_status_t autosage_decide_from_times(int32_t n_cand, const double* t_cand, double t_baseline,
+                                             double alpha, int32_t* choice);
+
+/* Full decision for one input: cache lookup by (device signature, graph signature, F, op, dt);
+ * on a miss: shortlist, probe the baseline and the top-k on a strided row sample of the real
+ * operands (outputs are used as probe targets and are left undefined), guardrail, optional
+ * full-input confirmation, store.  In replay-only mode a miss returns the baseline schedule and
+ * records the miss.  The operand arguments are those of autosage_spmm (op = SPMM: dense0 = B,
+ * dense1 = NULL, out = C) or autosage_sddmm (dense0 = X, dense1 = Y, out = out). */
+autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t op, int64_t n_rows, int64_t n_cols,
+                                  int64_t nnz, const int32_t* rowptr, const int32_t* colind, const float* val,
+                                  const void* dense0, int64_t ld0, const void* dense1, int64_t ld1,
+                                  float* out, int64_t ld_out, int32_t F, autosage_dtype_t dt,
+                                  void* workspace, size_t workspace_bytes, void* stream,
+                                  autosage_schedule_t* chosen);
+
+/* JSON text of the most recent decision of this handle (key, candidates, probe times, choice,
+ * alpha, cache hit / replay miss flags).  Truncated to n-1 characters. */
+autosage_status_t autosage_last_decision(autosage_handle_t h, char* json_buf, size_t n);
+
+/* Persistent schedule cache: a text file, one record per key.  Load merges into the handle's
+ * cache and skips malformed lines; save writes to a temporary file and renames it. */
+autosage_status_t autosage_cache_load(autosage_handle_t h, const char* path);
+autosage_status_t autosage_cache_save(autosage_handle_t h, const char* path);
+autosage_status_t autosage_cache_clear(autosage_handle_t h);
+/* Direct access for tests and tools (host only). found = 0/1. */
+autosage_status_t autosage_cache_lookup(autosage_handle_t h, uint64_t graph_sig, int32_t F, autosage_op_t op,
+                                        autosage_dtype_t dt, autosage_schedule_t* sched, int32_t* found);
+autosage_status_t autosage_cache_insert(autosage_handle_t h, uint64_t graph_sig, int32_t F, autosage_op_t op,
+                                        autosage_dtype_t dt, const autosage_schedule_t* sched);
+
+/* The baseline (fallback) schedule of the guardrail: plain one-wavefront-per-row kernel. */
+autosage_status_t autosage_baseline_schedule(autosage_schedule_t* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AUTOSAGE_H */

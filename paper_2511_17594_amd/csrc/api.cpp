@@ -1,0 +1,735 @@
+// C ABI of the library: argument checking, schedule resolution, workspace layout and the
+// sequencing of the kernel stages.  See include/autosage.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "internal.h"
+
+using namespace autosage;
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e__ = (expr);                        \
+        if (e__ != hipSuccess) return AUTOSAGE_ERR_HIP; \
+    } while (0)
+
+namespace autosage {
+
+int common_alignment(const void* p, int64_t ld, int elem_size)
+{
+    uint64_t v = reinterpret_cast<uint64_t>(p) | static_cast<uint64_t>(ld * elem_size) | 16u;
+    int a = 1;
+    while ((v & 1u) == 0 && a < 16) {
+        v >>= 1;
+        a <<= 1;
+    }
+    return a;
+}
+
+static int pow2_ceil(int x)
+{
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+static bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+// chunk counts per lane that have kernels: 1, 2, 3, 4, 6, 8
+static int round_chunks(int k)
+{
+    if (k <= 4) return k;
+    if (k <= 6) return 6;
+    return 8;
+}
+
+autosage_schedule_t baseline_schedule()
+{
+    autosage_schedule_t s{};
+    s.mapping = AUTOSAGE_MAP_PLAIN;
+    s.f_tile = 64;
+    s.waves_per_wg = 4;
+    s.vec_bytes = 0;
+    s.unroll = 0;
+    s.hub_t = 0;
+    s.hub_chunk = 0;
+    s.xcd_remap = 0;
+    return s;
+}
+
+autosage_status_t resolve_schedule(const autosage_schedule_t& s, int op, int32_t F, int dt, int heads,
+                                   int align_in, int align_out, Resolved* out)
+{
+    const int esize = dt == DT_BF16 ? 2 : 4;
+    Resolved r{};
+    if (F <= 0 || heads < 1) return AUTOSAGE_ERR_INVALID_ARG;
+    if (s.mapping < AUTOSAGE_MAP_PLAIN || s.mapping > AUTOSAGE_MAP_MULTI_ROW) return AUTOSAGE_ERR_INVALID_ARG;
+    r.mapping = s.mapping;
+    r.wpg = s.waves_per_wg == 0 ? 4 : s.waves_per_wg;
+    if (!(r.wpg == 1 || r.wpg == 2 || r.wpg == 4 || r.wpg == 8 || r.wpg == 16)) return AUTOSAGE_ERR_INVALID_ARG;
+    r.unroll = s.unroll == 0 ? 4 : s.unroll;
+    if (!(r.unroll == 1 || r.unroll == 2 || r.unroll == 4 || r.unroll == 8)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (s.hub_t < 0 || s.hub_chunk < 0 || (s.hub_t > 0 && s.hub_t < kMinHubT)) return AUTOSAGE_ERR_INVALID_ARG;
+    r.hub_t = s.hub_t;
+    r.hub_chunk = s.hub_t > 0 ? (s.hub_chunk > 0 ? s.hub_chunk : s.hub_t) : 0;
+    if (r.hub_t > 0 && r.hub_chunk < kMinHubT) return AUTOSAGE_ERR_INVALID_ARG;
+    r.xcd_remap = s.xcd_remap ? 1 : 0;
+    r.HW = 1;
+
+    // vector width
+    int vb = s.vec_bytes;
+    if (vb != 0 && vb != 2 && vb != 4 && vb != 8 && vb != 16) return AUTOSAGE_ERR_INVALID_ARG;
+    auto legal = [&](int bytes) {
+        if (bytes < esize) return false;
+        const int vec = bytes / esize;
+        if (F % vec != 0) return false;
+        if (align_in % bytes != 0 && bytes > esize) return false;
+        const int store_bytes = vec * 4 < 16 ? vec * 4 : 16;       // SpMM stores VEC fp32 values per lane
+        if (op == AUTOSAGE_OP_SPMM && store_bytes > 4 && align_out % store_bytes != 0) return false;
+        return true;
+    };
+    if (s.mapping == AUTOSAGE_MAP_PLAIN) {
+        if (vb != 0 && vb != esize) return AUTOSAGE_ERR_UNSUPPORTED;
+        vb = esize;
+    } else if (vb == 0) {
+        for (int cand = 16; cand >= esize; cand >>= 1) {
+            if (legal(cand)) {
+                vb = cand;
+                break;
+            }
+        }
+        if (vb == 0) vb = esize;
+    } else if (!legal(vb)) {
+        return AUTOSAGE_ERR_UNSUPPORTED;
+    }
+    r.vec = vb / esize;
+
+    const int lanes_needed = (F + r.vec - 1) / r.vec;
+    if (s.mapping == AUTOSAGE_MAP_PLAIN) {
+        r.G = 64;
+        r.K = 1;
+        r.f_tile = 64;
+        r.tiles = (F + 63) / 64;
+        *out = r;
+        return AUTOSAGE_OK;
+    }
+    int lanes_tile;
+    if (s.f_tile == 0) {
+        lanes_tile = lanes_needed <= 64 ? pow2_ceil(lanes_needed) : 64 * round_chunks((lanes_needed + 63) / 64 > 8 ? 4 : (lanes_needed + 63) / 64);
+    } else {
+        if (s.f_tile < 0 || s.f_tile % r.vec != 0) return AUTOSAGE_ERR_INVALID_ARG;
+        lanes_tile = s.f_tile / r.vec;
+        if (lanes_tile <= 64) {
+            if (!is_pow2(lanes_tile)) return AUTOSAGE_ERR_INVALID_ARG;
+        } else {
+            if (lanes_tile % 64 != 0) return AUTOSAGE_ERR_INVALID_ARG;
+            const int k = lanes_tile / 64;
+            if (k > 8 || round_chunks(k) != k) return AUTOSAGE_ERR_INVALID_ARG;
+        }
+        // a tile wider than needed is trimmed to the smallest shape covering F
+        if (lanes_tile > pow2_ceil(lanes_needed) && lanes_needed <= 64) lanes_tile = pow2_ceil(lanes_needed);
+    }
+    if (lanes_tile <= 64) {
+        r.G = lanes_tile;
+        r.K = 1;
+    } else {
+        r.G = 64;
+        r.K = lanes_tile / 64;
+    }
+    r.f_tile = r.G * r.vec * r.K;
+    r.tiles = (F + r.f_tile - 1) / r.f_tile;
+
+    if (op == AUTOSAGE_OP_SDDMM) {
+        // the dot product of one head must sit in one pass of one group
+        if (r.tiles != 1) {
+            r.G = 64;
+            r.K = round_chunks((lanes_needed + 63) / 64);
+            if ((lanes_needed + 63) / 64 > 8) return AUTOSAGE_ERR_UNSUPPORTED;
+            r.f_tile = r.G * r.vec * r.K;
+            r.tiles = 1;
+        }
+        if (heads > 1 && vb == 16 && r.K == 1 && r.G >= 2 && r.G <= 32) {
+            int hw = pow2_ceil(heads);
+            if (hw > 64 / r.G) hw = 64 / r.G;
+            r.HW = hw;
+        }
+    }
+    if (s.mapping == AUTOSAGE_MAP_MULTI_ROW && (r.G * r.HW > 32 || r.K != 1 || r.HW != 1)) return AUTOSAGE_ERR_UNSUPPORTED;
+    *out = r;
+    return AUTOSAGE_OK;
+}
+
+void hub_caps(int64_t count, int64_t nnz, int hub_t, int hub_chunk, int* cap_hub, int* cap_chunks)
+{
+    if (hub_t <= 0) {
+        *cap_hub = 0;
+        *cap_chunks = 0;
+        return;
+    }
+    int64_t ch = nnz / hub_t;
+    if (ch > count) ch = count;
+    int64_t cc = nnz / hub_chunk + ch;
+    *cap_hub = static_cast<int>(ch);
+    *cap_chunks = static_cast<int>(cc);
+}
+
+static size_t hub_meta_bytes(int64_t count, int cap_hub)
+{
+    const int64_t part_blocks = (count + 1023) / 1024;
+    size_t b = 256;                                                    // HubCounts
+    b += align_up(sizeof(int32_t) * 2 * (size_t)(part_blocks > 0 ? part_blocks : 1), 256);
+    b += align_up(sizeof(int32_t) * (size_t)(cap_hub > 0 ? cap_hub : 1), 256);          // hub_rows
+    b += align_up(sizeof(int32_t) * ((size_t)cap_hub + 1), 256);                      // chunk_ptr
+    return b;
+}
+
+size_t hub_workspace_bytes(int64_t count, int64_t nnz, int hub_t, int hub_chunk, int64_t part_floats_per_chunk)
+{
+    if (hub_t <= 0) return 0;
+    int cap_hub, cap_chunks;
+    hub_caps(count, nnz, hub_t, hub_chunk, &cap_hub, &cap_chunks);
+    return hub_meta_bytes(count, cap_hub) + align_up(sizeof(float) * (size_t)cap_chunks * (size_t)part_floats_per_chunk, 256);
+}
+
+bool carve_hub(void* ws, size_t ws_bytes, int64_t count, int64_t nnz, int hub_t, int hub_chunk,
+               int64_t part_floats_per_chunk, HubMeta* meta, float** part, size_t* used)
+{
+    int cap_hub, cap_chunks;
+    hub_caps(count, nnz, hub_t, hub_chunk, &cap_hub, &cap_chunks);
+    const size_t need = hub_workspace_bytes(count, nnz, hub_t, hub_chunk, part_floats_per_chunk);
+    if (used) *used = need;
+    if (ws == nullptr || ws_bytes < need || (reinterpret_cast<uint64_t>(ws) & 255u) != 0) return false;
+    char* p = static_cast<char*>(ws);
+    const int64_t part_blocks = (count + 1023) / 1024;
+    meta->counts = reinterpret_cast<HubCounts*>(p);
+    p += 256;
+    meta->block_counts = reinterpret_cast<int32_t*>(p);
+    p += align_up(sizeof(int32_t) * 2 * (size_t)(part_blocks > 0 ? part_blocks : 1), 256);
+    meta->hub_rows = reinterpret_cast<int32_t*>(p);
+    p += align_up(sizeof(int32_t) * (size_t)(cap_hub > 0 ? cap_hub : 1), 256);
+    meta->chunk_ptr = reinterpret_cast<int32_t*>(p);
+    p += align_up(sizeof(int32_t) * ((size_t)cap_hub + 1), 256);
+    meta->light_rows = nullptr;
+    meta->cap_hub = cap_hub;
+    meta->cap_chunks = cap_chunks;
+    if (part) *part = reinterpret_cast<float*>(p);
+    return true;
+}
+
+autosage_status_t exec_spmm(const SpmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes, hipStream_t st)
+{
+    if (a.rows.count == 0) return AUTOSAGE_OK;
+    HubMeta meta{};
+    float* part = nullptr;
+    if (r.hub_t > 0) {
+        if (!carve_hub(ws, ws_bytes, a.rows.count, nnz, r.hub_t, r.hub_chunk, a.F, &meta, &part, nullptr))
+            return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+        HIP_TRY(launch_hub_partition(a.rows, a.rowptr, r.hub_t, r.hub_chunk, meta, st));
+    }
+    HIP_TRY(launch_spmm_rows(a, r, st));
+    if (r.hub_t > 0) HIP_TRY(launch_spmm_hub(a, r, meta, part, st));
+    return AUTOSAGE_OK;
+}
+
+autosage_status_t exec_sddmm(const SddmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes, hipStream_t st)
+{
+    if (a.rows.count == 0) return AUTOSAGE_OK;
+    HubMeta meta{};
+    if (r.hub_t > 0) {
+        if (!carve_hub(ws, ws_bytes, a.rows.count, nnz, r.hub_t, r.hub_chunk, 0, &meta, nullptr, nullptr))
+            return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+        HIP_TRY(launch_hub_partition(a.rows, a.rowptr, r.hub_t, r.hub_chunk, meta, st));
+    }
+    HIP_TRY(launch_sddmm_rows(a, r, st));
+    if (r.hub_t > 0) HIP_TRY(launch_sddmm_hub(a, r, meta, st));
+    return AUTOSAGE_OK;
+}
+
+}  // namespace autosage
+
+// ------------------------------------------------------------------------------------------
+// lifetime
+// ------------------------------------------------------------------------------------------
+static double env_double(const char* name, double dflt)
+{
+    const char* v = std::getenv(name);
+    if (!v || !*v) return dflt;
+    char* end = nullptr;
+    const double x = std::strtod(v, &end);
+    return end == v ? dflt : x;
+}
+
+extern "C" autosage_status_t autosage_create(autosage_handle_t* out, int device_id)
+{
+    if (!out) return AUTOSAGE_ERR_INVALID_ARG;
+    autosage_ctx* h = new (std::nothrow) autosage_ctx();
+    if (!h) return AUTOSAGE_ERR_HIP;
+    h->device = device_id;
+    Params& p = h->params;
+    p.alpha = env_double("AUTOSAGE_ALPHA", p.alpha);
+    p.probe_frac = env_double("AUTOSAGE_PROBE_FRAC", p.probe_frac);
+    p.probe_iters = (int)env_double("AUTOSAGE_PROBE_ITERS", p.probe_iters);
+    p.probe_cap_ms = env_double("AUTOSAGE_PROBE_CAP_MS", p.probe_cap_ms);
+    p.probe_topk = (int)env_double("AUTOSAGE_PROBE_TOPK", p.probe_topk);
+    p.probe_min_rows = (int)env_double("AUTOSAGE_PROBE_MIN_ROWS", p.probe_min_rows);
+    p.replay_only = (int)env_double("AUTOSAGE_REPLAY_ONLY", 0);
+    p.force_ftile = (int)env_double("AUTOSAGE_FTILE", 0);
+    p.force_wpb = (int)env_double("AUTOSAGE_WPB", 0);
+    p.force_hub_t = (int)env_double("AUTOSAGE_HUB_T", -1);
+    if (device_id >= 0) {
+        hipDeviceProp_t prop;
+        if (hipSetDevice(device_id) != hipSuccess || hipGetDeviceProperties(&prop, device_id) != hipSuccess) {
+            delete h;
+            return AUTOSAGE_ERR_HIP;
+        }
+        int rt = 0;
+        hipRuntimeGetVersion(&rt);
+        h->cu_count = prop.multiProcessorCount;
+        char buf[256];
+        std::snprintf(buf, sizeof buf, "%s_%dcu_hip%d_lib1", prop.gcnArchName, prop.multiProcessorCount, rt);
+        h->device_sig = buf;
+        for (char& c : h->device_sig)
+            if (c == ' ' || c == '\t') c = '_';
+        if (hipMalloc(&h->dev_features, sizeof(int64_t) * (35 + 1024)) != hipSuccess ||
+            hipHostMalloc(&h->host_features, sizeof(int64_t) * (35 + 1024)) != hipSuccess ||
+            hipMalloc(&h->dev_flag, 256) != hipSuccess || hipEventCreate(&h->ev0) != hipSuccess ||
+            hipEventCreate(&h->ev1) != hipSuccess) {
+            autosage_destroy(h);
+            return AUTOSAGE_ERR_HIP;
+        }
+    }
+    const char* cp = std::getenv("AUTOSAGE_CACHE");
+    if (cp && *cp) {
+        h->cache_path = cp;
+        autosage_cache_load(h, cp);        // a missing or broken file is not an error at start-up
+    }
+    *out = h;
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_destroy(autosage_handle_t h)
+{
+    if (!h) return AUTOSAGE_ERR_INVALID_ARG;
+    autosage_status_t st = AUTOSAGE_OK;
+    if (!h->cache_path.empty()) st = autosage_cache_save(h, h->cache_path.c_str());
+    if (h->dev_features) hipFree(h->dev_features);
+    if (h->host_features) hipHostFree(h->host_features);
+    if (h->dev_flag) hipFree(h->dev_flag);
+    if (h->ev0) hipEventDestroy(h->ev0);
+    if (h->ev1) hipEventDestroy(h->ev1);
+    delete h;
+    return st;
+}
+
+extern "C" const char* autosage_status_string(autosage_status_t s)
+{
+    switch (s) {
+        case AUTOSAGE_OK: return "ok";
+        case AUTOSAGE_ERR_INVALID_ARG: return "invalid argument";
+        case AUTOSAGE_ERR_UNSUPPORTED: return "unsupported schedule, dtype or shape";
+        case AUTOSAGE_ERR_WORKSPACE_TOO_SMALL: return "workspace too small or misaligned";
+        case AUTOSAGE_ERR_HIP: return "HIP runtime error";
+        case AUTOSAGE_ERR_IO: return "file I/O error";
+        case AUTOSAGE_ERR_REPLAY_MISS: return "replay-only mode: key not in cache";
+        default: return "unknown status";
+    }
+}
+
+namespace {
+struct ParamRef {
+    const char* name;
+    int kind;   // 0 double, 1 int
+    void* (*get)(Params&);
+};
+}  // namespace
+
+static bool param_access(Params& p, const char* name, double* value, bool set)
+{
+#define P_DOUBLE(nm, field)                 \
+    if (std::strcmp(name, nm) == 0) {       \
+        if (set) p.field = *value;          \
+        else *value = p.field;              \
+        return true;                        \
+    }
+#define P_INT(nm, field)                    \
+    if (std::strcmp(name, nm) == 0) {       \
+        if (set) p.field = (int)*value;     \
+        else *value = (double)p.field;      \
+        return true;                        \
+    }
+    P_DOUBLE("alpha", alpha)
+    P_DOUBLE("probe_frac", probe_frac)
+    P_INT("probe_iters", probe_iters)
+    P_DOUBLE("probe_cap_ms", probe_cap_ms)
+    P_INT("probe_topk", probe_topk)
+    P_INT("probe_min_rows", probe_min_rows)
+    P_INT("replay_only", replay_only)
+    P_INT("confirm_full", confirm_full)
+    P_INT("memoize_signature", memoize_signature)
+    P_INT("force_ftile", force_ftile)
+    P_INT("force_wpb", force_wpb)
+    P_INT("force_hub_t", force_hub_t)
+#undef P_DOUBLE
+#undef P_INT
+    return false;
+}
+
+extern "C" autosage_status_t autosage_set_param(autosage_handle_t h, const char* name, double value)
+{
+    if (!h || !name || std::isnan(value)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (std::strcmp(name, "alpha") == 0 && value <= 0) return AUTOSAGE_ERR_INVALID_ARG;
+    if (std::strcmp(name, "probe_frac") == 0 && (value <= 0 || value > 1)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (std::strcmp(name, "probe_iters") == 0 && value < 1) return AUTOSAGE_ERR_INVALID_ARG;
+    return param_access(h->params, name, &value, true) ? AUTOSAGE_OK : AUTOSAGE_ERR_INVALID_ARG;
+}
+
+extern "C" autosage_status_t autosage_get_param(autosage_handle_t h, const char* name, double* value)
+{
+    if (!h || !name || !value) return AUTOSAGE_ERR_INVALID_ARG;
+    return param_access(h->params, name, value, false) ? AUTOSAGE_OK : AUTOSAGE_ERR_INVALID_ARG;
+}
+
+extern "C" autosage_status_t autosage_baseline_schedule(autosage_schedule_t* out)
+{
+    if (!out) return AUTOSAGE_ERR_INVALID_ARG;
+    *out = baseline_schedule();
+    return AUTOSAGE_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// hot path
+// ------------------------------------------------------------------------------------------
+static bool sizes_ok(int64_t n_rows, int64_t n_cols, int64_t nnz)
+{
+    return n_rows >= 0 && n_cols >= 0 && nnz >= 0 && nnz < (int64_t(1) << 31) && n_rows < (int64_t(1) << 31) - 1 &&
+           n_cols < (int64_t(1) << 31);
+}
+
+extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                           const int32_t* rowptr, const int32_t* colind, const float* val,
+                                           const void* B, int64_t ldb, float* C, int64_t ldc, int32_t F,
+                                           autosage_dtype_t dt, const autosage_schedule_t* sched,
+                                           void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!h || !sizes_ok(n_rows, n_cols, nnz) || F <= 0 || ldb < F || ldc < F) return AUTOSAGE_ERR_INVALID_ARG;
+    if (dt != AUTOSAGE_F32 && dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (n_rows == 0) return AUTOSAGE_OK;
+    if (!rowptr || !C || (nnz > 0 && (!colind || !val || !B))) return AUTOSAGE_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    autosage_schedule_t chosen;
+    if (!sched) {
+        autosage_status_t s = autosage_decide(h, AUTOSAGE_OP_SPMM, n_rows, n_cols, nnz, rowptr, colind, val, B, ldb,
+                                              nullptr, 0, C, ldc, F, dt, workspace, workspace_bytes, stream, &chosen);
+        if (s != AUTOSAGE_OK) return s;
+        sched = &chosen;
+    }
+    const int esize = dt == AUTOSAGE_BF16 ? 2 : 4;
+    Resolved r;
+    autosage_status_t s = resolve_schedule(*sched, AUTOSAGE_OP_SPMM, F, dt, 1, common_alignment(B, ldb, esize),
+                                           common_alignment(C, ldc, 4), &r);
+    if (s != AUTOSAGE_OK) return s;
+    SpmmArgs a{};
+    a.rows = RowMap{0, 1, (int32_t)n_rows};
+    a.rowptr = rowptr;
+    a.colind = colind;
+    a.val = val;
+    a.B = B;
+    a.ldb = ldb;
+    a.C = C;
+    a.ldc = ldc;
+    a.F = F;
+    a.dt = dt;
+    a.heads = 1;
+    a.head_dim = F;
+    return exec_spmm(a, r, nnz, workspace, workspace_bytes, st);
+}
+
+extern "C" autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                            const int32_t* rowptr, const int32_t* colind, const float* val,
+                                            const void* X, int64_t ldx, const void* Y, int64_t ldy, int32_t F,
+                                            autosage_dtype_t dt, float* out, const autosage_schedule_t* sched,
+                                            void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)val;
+    if (!h || !sizes_ok(n_rows, n_cols, nnz) || F <= 0 || ldx < F || ldy < F) return AUTOSAGE_ERR_INVALID_ARG;
+    if (dt != AUTOSAGE_F32 && dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (n_rows == 0 || nnz == 0) return AUTOSAGE_OK;
+    if (!rowptr || !colind || !X || !Y || !out) return AUTOSAGE_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    autosage_schedule_t chosen;
+    if (!sched) {
+        autosage_status_t s = autosage_decide(h, AUTOSAGE_OP_SDDMM, n_rows, n_cols, nnz, rowptr, colind, nullptr, X, ldx,
+                                              Y, ldy, out, 1, F, dt, workspace, workspace_bytes, stream, &chosen);
+        if (s != AUTOSAGE_OK) return s;
+        sched = &chosen;
+    }
+    const int esize = dt == AUTOSAGE_BF16 ? 2 : 4;
+    int al = common_alignment(X, ldx, esize);
+    const int al2 = common_alignment(Y, ldy, esize);
+    if (al2 < al) al = al2;
+    Resolved r;
+    autosage_status_t s = resolve_schedule(*sched, AUTOSAGE_OP_SDDMM, F, dt, 1, al, 16, &r);
+    if (s != AUTOSAGE_OK) return s;
+    SddmmArgs a{};
+    a.rows = RowMap{0, 1, (int32_t)n_rows};
+    a.rowptr = rowptr;
+    a.colind = colind;
+    a.X = X;
+    a.ldx = ldx;
+    a.Y = Y;
+    a.ldy = ldy;
+    a.out = out;
+    a.F = F;
+    a.dt = dt;
+    a.heads = 1;
+    a.scale = 1.0f;
+    return exec_sddmm(a, r, nnz, workspace, workspace_bytes, st);
+}
+
+static autosage_status_t exec_softmax(const SoftmaxArgs& a, int64_t nnz, int hub_t, int hub_chunk, int wpg,
+                                      const HubMeta* shared_meta, float* shared_part, void* ws, size_t ws_bytes,
+                                      hipStream_t st)
+{
+    if (a.rows.count == 0 || nnz == 0) return AUTOSAGE_OK;
+    HubMeta meta{};
+    float* part = nullptr;
+    if (hub_t > 0) {
+        if (shared_meta) {
+            meta = *shared_meta;
+            part = shared_part;
+        } else {
+            if (!carve_hub(ws, ws_bytes, a.rows.count, nnz, hub_t, hub_chunk, 2 * (int64_t)a.H, &meta, &part, nullptr))
+                return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+            HIP_TRY(launch_hub_partition(a.rows, a.rowptr, hub_t, hub_chunk, meta, st));
+        }
+    }
+    HIP_TRY(launch_softmax_rows(a, hub_t, wpg, st));
+    if (hub_t > 0) HIP_TRY(launch_softmax_hub(a, hub_chunk, meta, part, st));
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64_t n_rows, int64_t nnz,
+                                                      const int32_t* rowptr, const float* in, float* out,
+                                                      int32_t H, int32_t hub_t, int32_t hub_chunk,
+                                                      void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!h || !sizes_ok(n_rows, 0, nnz) || H <= 0 || hub_t < 0 || hub_chunk < 0) return AUTOSAGE_ERR_INVALID_ARG;
+    if ((int64_t)nnz * H >= (int64_t(1) << 40)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (hub_t > 0 && hub_t < kMinHubT) return AUTOSAGE_ERR_INVALID_ARG;
+    if (!rowptr || (nnz > 0 && (!in || !out))) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    const int chunk = hub_t > 0 ? (hub_chunk > 0 ? hub_chunk : hub_t) : 0;
+    if (hub_t > 0 && chunk < kMinHubT) return AUTOSAGE_ERR_INVALID_ARG;
+    SoftmaxArgs a{};
+    a.rows = RowMap{0, 1, (int32_t)n_rows};
+    a.rowptr = rowptr;
+    a.in = in;
+    a.out = out;
+    a.H = H;
+    return exec_softmax(a, nnz, hub_t, chunk, 4, nullptr, nullptr, workspace, workspace_bytes,
+                        static_cast<hipStream_t>(stream));
+}
+
+// Workspace of the attention pipeline: [scores nnz*H fp32][hub metadata + partial buffer].
+static size_t attention_part_floats(int32_t H, int32_t d) { return (size_t)H * d > 2 * (size_t)H ? (size_t)H * d : 2 * (size_t)H; }
+
+extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t N, int64_t nnz,
+                                                    const int32_t* rowptr, const int32_t* colind, const float* val,
+                                                    const void* Q, const void* K, const void* V, float* O,
+                                                    int32_t H, int32_t d, float scale, autosage_dtype_t in_dt,
+                                                    const autosage_schedule_t* sched,
+                                                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)val;
+    if (!h || !sizes_ok(N, N, nnz) || H <= 0 || d <= 0 || (int64_t)H * d >= (1 << 24)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (in_dt != AUTOSAGE_F32 && in_dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (!rowptr || !O || (nnz > 0 && (!colind || !Q || !K || !V))) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (N == 0) return AUTOSAGE_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int esize = in_dt == AUTOSAGE_BF16 ? 2 : 4;
+    const int64_t HD = (int64_t)H * d;
+    // 16-byte lane loads are required: d must be a multiple of 16 / esize elements and the operands aligned
+    if ((d * esize) % 16 != 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    int al = common_alignment(Q, HD, esize);
+    int t = common_alignment(K, HD, esize);
+    if (t < al) al = t;
+    t = common_alignment(V, HD, esize);
+    if (t < al) al = t;
+    if (al < 16 || common_alignment(O, HD, 4) < 16) return AUTOSAGE_ERR_UNSUPPORTED;
+
+    autosage_schedule_t s{};
+    if (sched) s = *sched;
+    else {
+        s.hub_t = 1024;
+        s.hub_chunk = 1024;
+    }
+    s.mapping = AUTOSAGE_MAP_WAVE_ROW;
+    s.f_tile = 0;
+    s.vec_bytes = 16;
+    Resolved rs, rp;
+    autosage_status_t rc = resolve_schedule(s, AUTOSAGE_OP_SDDMM, d, in_dt, H, al, 16, &rs);
+    if (rc != AUTOSAGE_OK) return rc;
+    rc = resolve_schedule(s, AUTOSAGE_OP_SPMM, (int32_t)HD, in_dt, 1, al, 16, &rp);
+    if (rc != AUTOSAGE_OK) return rc;
+
+    const size_t score_bytes = align_up(sizeof(float) * (size_t)nnz * H, 256);
+    if (!workspace || (reinterpret_cast<uint64_t>(workspace) & 255u) != 0 || workspace_bytes < score_bytes)
+        return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+    float* S = static_cast<float*>(workspace);
+    char* hub_ws = static_cast<char*>(workspace) + score_bytes;
+    const size_t hub_ws_bytes = workspace_bytes - score_bytes;
+
+    const RowMap rows{0, 1, (int32_t)N};
+    HubMeta meta{};
+    float* part = nullptr;
+    if (rs.hub_t > 0) {
+        if (!carve_hub(hub_ws, hub_ws_bytes, N, nnz, rs.hub_t, rs.hub_chunk, (int64_t)attention_part_floats(H, d), &meta,
+                       &part, nullptr))
+            return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+        HIP_TRY(launch_hub_partition(rows, rowptr, rs.hub_t, rs.hub_chunk, meta, st));
+    }
+    // stage 1: scores
+    SddmmArgs sa{};
+    sa.rows = rows;
+    sa.rowptr = rowptr;
+    sa.colind = colind;
+    sa.X = Q;
+    sa.ldx = HD;
+    sa.Y = K;
+    sa.ldy = HD;
+    sa.out = S;
+    sa.F = d;
+    sa.dt = in_dt;
+    sa.heads = H;
+    sa.scale = scale;
+    if (nnz > 0) {
+        HIP_TRY(launch_sddmm_rows(sa, rs, st));
+        if (rs.hub_t > 0) HIP_TRY(launch_sddmm_hub(sa, rs, meta, st));
+    }
+    // stage 2: row-softmax in place
+    SoftmaxArgs ma{};
+    ma.rows = rows;
+    ma.rowptr = rowptr;
+    ma.in = S;
+    ma.out = S;
+    ma.H = H;
+    rc = exec_softmax(ma, nnz, rs.hub_t, rs.hub_chunk, rs.wpg, rs.hub_t > 0 ? &meta : nullptr, part, nullptr, 0, st);
+    if (rc != AUTOSAGE_OK) return rc;
+    // stage 3: weighted sum of V rows with per-head weights
+    SpmmArgs pa{};
+    pa.rows = rows;
+    pa.rowptr = rowptr;
+    pa.colind = colind;
+    pa.val = S;
+    pa.B = V;
+    pa.ldb = HD;
+    pa.C = O;
+    pa.ldc = HD;
+    pa.F = (int32_t)HD;
+    pa.dt = in_dt;
+    pa.heads = H > 1 ? H : 1;
+    pa.head_dim = d;
+    HIP_TRY(launch_spmm_rows(pa, rp, st));
+    if (rp.hub_t > 0) HIP_TRY(launch_spmm_hub(pa, rp, meta, part, st));
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autosage_op_t op, int64_t n_rows,
+                                                      int64_t nnz, int32_t F, int32_t H,
+                                                      const autosage_schedule_t* sched, size_t* bytes)
+{
+    if (!h || !bytes || !sizes_ok(n_rows, 0, nnz) || F <= 0 || H <= 0) return AUTOSAGE_ERR_INVALID_ARG;
+    int hub_t = kSelectorMinHubT, chunk = kSelectorMinHubT;
+    if (sched) {
+        hub_t = sched->hub_t;
+        chunk = sched->hub_t > 0 ? (sched->hub_chunk > 0 ? sched->hub_chunk : sched->hub_t) : 0;
+        if (hub_t < 0 || (hub_t > 0 && (hub_t < kMinHubT || chunk < kMinHubT))) return AUTOSAGE_ERR_INVALID_ARG;
+    } else if (op == AUTOSAGE_OP_ATTENTION) {
+        hub_t = chunk = 1024;
+    }
+    size_t b = 0;
+    switch (op) {
+        case AUTOSAGE_OP_SPMM: b = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, F); break;
+        case AUTOSAGE_OP_SDDMM: b = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, 0); break;
+        case AUTOSAGE_OP_SOFTMAX: b = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, 2 * (int64_t)H); break;
+        case AUTOSAGE_OP_ATTENTION:
+            b = align_up(sizeof(float) * (size_t)nnz * H, 256) +
+                hub_workspace_bytes(n_rows, nnz, hub_t, chunk, (int64_t)attention_part_floats(H, F));
+            break;
+        default: return AUTOSAGE_ERR_INVALID_ARG;
+    }
+    *bytes = b < 256 ? 256 : b;
+    return AUTOSAGE_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// plan / metadata
+// ------------------------------------------------------------------------------------------
+extern "C" autosage_status_t autosage_hub_partition(autosage_handle_t h, int64_t n_rows, const int32_t* rowptr,
+                                                    int32_t hub_t, int32_t hub_chunk,
+                                                    int32_t* n_hub, int32_t* hub_rows, int32_t* chunk_ptr,
+                                                    int32_t* n_light, int32_t* light_rows,
+                                                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!h || !sizes_ok(n_rows, 0, 0) || !rowptr || hub_t < 1 || hub_chunk < 1 || !n_hub || !hub_rows || !chunk_ptr || !n_light)
+        return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t part_blocks = (n_rows + 1023) / 1024;
+    const size_t need = 256 + align_up(sizeof(int32_t) * 2 * (size_t)(part_blocks > 0 ? part_blocks : 1), 256);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uint64_t>(workspace) & 255u) != 0)
+        return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+    HubMeta meta{};
+    meta.counts = static_cast<HubCounts*>(workspace);
+    meta.block_counts = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + 256);
+    meta.hub_rows = hub_rows;
+    meta.chunk_ptr = chunk_ptr;
+    meta.light_rows = light_rows;
+    meta.cap_hub = (int32_t)n_rows;
+    meta.cap_chunks = 0;
+    HIP_TRY(launch_hub_partition(RowMap{0, 1, (int32_t)n_rows}, rowptr, hub_t, hub_chunk, meta, st));
+    HubCounts c{};
+    HIP_TRY(hipMemcpyAsync(&c, meta.counts, sizeof c, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    *n_hub = c.n_hub;
+    *n_light = c.n_light;
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_graph_features(autosage_handle_t h, int64_t n_rows, int64_t n_cols,
+                                                     const int32_t* rowptr, int64_t* hist33, int64_t* max_deg,
+                                                     int64_t* nnz, uint64_t* signature, void* stream)
+{
+    if (!h || !sizes_ok(n_rows, n_cols, 0) || !rowptr) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(launch_graph_features(n_rows, rowptr, h->dev_features, st));
+    HIP_TRY(hipMemcpyAsync(h->host_features, h->dev_features, sizeof(int64_t) * (35 + 1024), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    const int64_t* f = h->host_features;
+    if (hist33) std::memcpy(hist33, f, sizeof(int64_t) * 33);
+    if (max_deg) *max_deg = f[33];
+    if (nnz) *nnz = f[34];
+    if (signature) *signature = signature_from_features(n_rows, n_cols, f);
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_validate_csr(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                                   const int32_t* rowptr, const int32_t* colind, void* stream)
+{
+    if (!h || !sizes_ok(n_rows, n_cols, nnz) || !rowptr || (nnz > 0 && !colind)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(launch_validate_csr(n_rows, n_cols, nnz, rowptr, colind, h->dev_flag, st));
+    int32_t flag = 0;
+    HIP_TRY(hipMemcpyAsync(&flag, h->dev_flag, sizeof flag, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    return flag ? AUTOSAGE_ERR_INVALID_ARG : AUTOSAGE_OK;
+}

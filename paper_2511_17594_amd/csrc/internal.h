@@ -1,0 +1,113 @@
+// Host-side internals of the library: the handle, schedule resolution, workspace layout,
+// stage execution and the selector.  Not part of the public ABI.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include <map>
+#include <string>
+#include <tuple>
+#include <vector>
+
+#include "../../include/autosage.h"
+#include "launch.h"
+
+namespace autosage {
+
+struct CacheKey {
+    uint64_t graph_sig;
+    int32_t F;
+    int32_t op;
+    int32_t dt;
+    bool operator<(const CacheKey& o) const
+    {
+        return std::tie(graph_sig, F, op, dt) < std::tie(o.graph_sig, o.F, o.op, o.dt);
+    }
+};
+
+struct CacheEntry {
+    autosage_schedule_t sched;
+    double t_baseline_ms;
+    double t_chosen_ms;
+};
+
+struct SigMemo {
+    const void* rowptr;
+    int64_t n_rows;
+    int64_t n_cols;
+    int64_t nnz;
+    uint64_t sig;
+    int64_t hist[33];
+    int64_t max_deg;
+};
+
+struct Params {
+    double alpha = 0.95;
+    double probe_frac = 0.02;
+    int probe_iters = 5;
+    double probe_cap_ms = 1.0;
+    int probe_topk = 3;
+    int probe_min_rows = 512;
+    int replay_only = 0;
+    int confirm_full = 1;
+    int memoize_signature = 1;
+    // forced knobs from the environment (0 = not forced)
+    int force_ftile = 0;
+    int force_wpb = 0;
+    int force_hub_t = -1;     // -1 = not forced, 0 = forced off
+};
+
+}  // namespace autosage
+
+struct autosage_ctx {
+    int device = -1;                       // < 0: host-only handle
+    std::string device_sig = "host";
+    int cu_count = 0;
+    autosage::Params params;
+    std::map<autosage::CacheKey, autosage::CacheEntry> cache;
+    std::string cache_path;                // from AUTOSAGE_CACHE; saved on destroy
+    std::string last_decision = "{}";
+    std::vector<autosage::SigMemo> memo;
+    int64_t* dev_features = nullptr;       // int64[35 + 1024]
+    int64_t* host_features = nullptr;      // pinned mirror
+    int32_t* dev_flag = nullptr;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+};
+
+namespace autosage {
+
+constexpr int kMinHubT = 64;               // smallest split threshold the library accepts
+constexpr int kSelectorMinHubT = 512;      // smallest threshold the selector proposes
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Largest power of two <= 16 that divides the pointer value and ld * elem_size.
+int common_alignment(const void* p, int64_t ld, int elem_size);
+
+// Resolves the "auto" fields of a schedule for an op of width F (per-head width for SDDMM with heads).
+// align_in: alignment of the dense inputs, align_out: of the dense output (SpMM) or 16 when scalar stores are used.
+autosage_status_t resolve_schedule(const autosage_schedule_t& s, int op, int32_t F, int dt, int heads,
+                                   int align_in, int align_out, Resolved* out);
+
+// Upper bounds of hub rows / chunks for `count` rows holding at most nnz nonzeros.
+void hub_caps(int64_t count, int64_t nnz, int hub_t, int hub_chunk, int* cap_hub, int* cap_chunks);
+
+// Workspace needed by one explicit schedule (bytes).  part_floats_per_chunk: F for SpMM, 2*H for softmax, 0 for SDDMM.
+size_t hub_workspace_bytes(int64_t count, int64_t nnz, int hub_t, int hub_chunk, int64_t part_floats_per_chunk);
+
+// Carves the hub metadata and the partial buffer out of ws; returns false when ws is too small.
+bool carve_hub(void* ws, size_t ws_bytes, int64_t count, int64_t nnz, int hub_t, int hub_chunk,
+               int64_t part_floats_per_chunk, HubMeta* meta, float** part, size_t* used);
+
+autosage_status_t exec_spmm(const SpmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes, hipStream_t st);
+autosage_status_t exec_sddmm(const SddmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes, hipStream_t st);
+
+// Host-only selector pieces
+int decide_from_times(int n, const double* t, double tb, double alpha);
+void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* hist33,
+               int64_t max_deg, int32_t F, int dt, int align_bytes, std::vector<autosage_schedule_t>* out,
+               std::vector<double>* est);
+uint64_t signature_from_features(int64_t n_rows, int64_t n_cols, const int64_t* feat /* hist33, max, nnz, 1024 samples */);
+autosage_schedule_t baseline_schedule();
+std::string schedule_json(const autosage_schedule_t& s);
+
+}  // namespace autosage

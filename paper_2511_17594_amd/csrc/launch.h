@@ -1,0 +1,116 @@
+// Host-side launcher interface between the C ABI layer and the kernel translation units.
+// Everything here is plain data + free functions; no device code.
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace autosage {
+
+enum Mapping { MAP_PLAIN = 0, MAP_WAVE_ROW = 1, MAP_MULTI_ROW = 2 };
+enum DType { DT_F32 = 0, DT_BF16 = 1 };
+
+// The rows a launch covers: row(idx) = first + idx * stride for idx in [0, count).
+// The full matrix is {0, 1, n_rows}; a probe uses a strided sample of the same arrays.
+struct RowMap {
+    int32_t first;
+    int32_t stride;
+    int32_t count;
+};
+
+// A schedule with every "auto" field resolved against F, dtype and alignment.
+struct Resolved {
+    int32_t mapping;    // Mapping
+    int32_t vec;        // elements per lane load
+    int32_t G;          // lanes per group (power of two, <= 64)
+    int32_t K;          // vector chunks per lane per pass
+    int32_t HW;         // SDDMM: heads side by side in one group (1 for SpMM and single-head SDDMM)
+    int32_t f_tile;     // features per pass = G * vec * K (PLAIN: 64)
+    int32_t tiles;      // passes over F (grid.y; PLAIN loops inside the kernel)
+    int32_t wpg;        // wavefronts per workgroup
+    int32_t unroll;     // nonzeros in flight per group
+    int32_t hub_t;      // 0 = no hub split
+    int32_t hub_chunk;
+    int32_t xcd_remap;
+};
+
+// Device-resident index metadata of the heavy/light split, laid out in the workspace.
+struct HubCounts {      // first 16 bytes of the metadata block
+    int32_t n_hub;
+    int32_t n_chunks;
+    int32_t n_light;
+    int32_t pad;
+};
+
+struct HubMeta {
+    HubCounts* counts;      // dev
+    int32_t* hub_rows;      // dev, capacity cap_hub (values are idx of the RowMap, i.e. row = first + v * stride)
+    int32_t* chunk_ptr;     // dev, capacity cap_hub + 1
+    int32_t* light_rows;    // dev or nullptr
+    int32_t* block_counts;  // dev scratch, 4 ints per partition block
+    int32_t cap_hub;        // host upper bound of n_hub
+    int32_t cap_chunks;     // host upper bound of n_chunks
+};
+
+struct SpmmArgs {
+    RowMap rows;
+    const int32_t* rowptr;
+    const int32_t* colind;
+    const float* val;      // [nnz] (heads == 1) or [nnz, heads] per-head weights
+    const void* B;         // [n_cols, F] (heads == 1) or [n_cols, heads, d] with F = heads * d
+    int64_t ldb;
+    float* C;
+    int64_t ldc;
+    int32_t F;
+    int32_t dt;
+    int32_t heads;         // 1 = plain SpMM; > 1 = per-head weights, head of feature f is f / head_dim
+    int32_t head_dim;
+};
+
+struct SddmmArgs {
+    RowMap rows;
+    const int32_t* rowptr;
+    const int32_t* colind;
+    const void* X;         // [n_rows, heads * d]
+    int64_t ldx;
+    const void* Y;         // [n_cols, heads * d]
+    int64_t ldy;
+    float* out;            // [nnz, heads]
+    int32_t F;             // per-head feature count d
+    int32_t dt;
+    int32_t heads;
+    float scale;           // out = scale * dot
+};
+
+struct SoftmaxArgs {
+    RowMap rows;
+    const int32_t* rowptr;
+    const float* in;       // [nnz, H]
+    float* out;            // [nnz, H]
+    int32_t H;
+};
+
+// Heavy/light partition of the rows of `rows` (index metadata, integer only).
+hipError_t launch_hub_partition(const RowMap& rows, const int32_t* rowptr, int32_t hub_t, int32_t hub_chunk,
+                                const HubMeta& meta, hipStream_t stream);
+
+// SpMM: light rows (skips rows of degree >= r.hub_t when r.hub_t > 0) ...
+hipError_t launch_spmm_rows(const SpmmArgs& a, const Resolved& r, hipStream_t stream);
+// ... and the hub rows: per-chunk partial rows into `part` ([cap_chunks, F] fp32), then an ordered combine.
+hipError_t launch_spmm_hub(const SpmmArgs& a, const Resolved& r, const HubMeta& meta, float* part, hipStream_t stream);
+
+hipError_t launch_sddmm_rows(const SddmmArgs& a, const Resolved& r, hipStream_t stream);
+hipError_t launch_sddmm_hub(const SddmmArgs& a, const Resolved& r, const HubMeta& meta, hipStream_t stream);
+
+// Row-softmax: light rows, and hub rows through per-chunk (max, sum) partials in `part` ([cap_chunks, H, 2]).
+hipError_t launch_softmax_rows(const SoftmaxArgs& a, int32_t hub_t, int32_t wpg, hipStream_t stream);
+hipError_t launch_softmax_hub(const SoftmaxArgs& a, int32_t hub_chunk, const HubMeta& meta, float* part, hipStream_t stream);
+
+// Degree features: hist[33] (int64), max_deg, nnz and the 1024 rowptr samples, written to `dev_out`
+// (int64[33 + 2 + 1024]); the caller copies it back.
+hipError_t launch_graph_features(int64_t n_rows, const int32_t* rowptr, int64_t* dev_out, hipStream_t stream);
+// CSR consistency check; dev_flag[0] becomes nonzero when a violation is found.
+hipError_t launch_validate_csr(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
+                               const int32_t* colind, int32_t* dev_flag, hipStream_t stream);
+
+}  // namespace autosage

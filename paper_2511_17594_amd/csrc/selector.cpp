@@ -1,0 +1,544 @@
+// Input-aware schedule selection (paper, Scheduler subsection, decision sketch, Proposition 1):
+// degree-histogram estimate -> timed probes on a strided row sample of the real operands ->
+// guardrail against the plain one-wavefront-per-row kernel -> persistent cache keyed by
+// (device signature, graph signature, F, op, dtype).  The cost model is this library's own,
+// written for MI355X; it only ranks candidates, the probes decide.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <fstream>
+#include <limits>
+#include <sstream>
+
+#include "internal.h"
+
+using namespace autosage;
+
+namespace autosage {
+
+int decide_from_times(int n, const double* t, double tb, double alpha)
+{
+    int best = -1;
+    double tstar = std::numeric_limits<double>::infinity();
+    for (int c = 0; c < n; ++c) {
+        if (t[c] < tstar) {      // strict: the first of equal candidates is kept
+            best = c;
+            tstar = t[c];
+        }
+    }
+    return tstar <= alpha * tb ? best : -1;
+}
+
+static uint64_t fnv1a_i64(uint64_t h, int64_t v)
+{
+    uint64_t u = static_cast<uint64_t>(v);
+    for (int b = 0; b < 8; ++b) {
+        h ^= (u >> (8 * b)) & 0xFFu;
+        h *= 0x100000001B3ULL;
+    }
+    return h;
+}
+
+uint64_t signature_from_features(int64_t n_rows, int64_t n_cols, const int64_t* f)
+{
+    uint64_t h = 0xCBF29CE484222325ULL;
+    h = fnv1a_i64(h, n_rows);
+    h = fnv1a_i64(h, n_cols);
+    h = fnv1a_i64(h, f[34]);                       // nnz
+    h = fnv1a_i64(h, f[33]);                       // max degree
+    for (int b = 0; b < 33; ++b) h = fnv1a_i64(h, f[b]);
+    for (int k = 0; k < 1024; ++k) h = fnv1a_i64(h, f[35 + k]);
+    return h;
+}
+
+std::string schedule_json(const autosage_schedule_t& s)
+{
+    char buf[256];
+    std::snprintf(buf, sizeof buf,
+                  "{\"mapping\":%d,\"f_tile\":%d,\"waves_per_wg\":%d,\"vec_bytes\":%d,\"unroll\":%d,\"hub_t\":%d,"
+                  "\"hub_chunk\":%d,\"xcd_remap\":%d}",
+                  s.mapping, s.f_tile, s.waves_per_wg, s.vec_bytes, s.unroll, s.hub_t, s.hub_chunk, s.xcd_remap);
+    return buf;
+}
+
+// ---- estimate ------------------------------------------------------------------------------
+namespace {
+
+struct Model {
+    double bw_stream = 5.0e12;     // B/s, contiguous reads and writes
+    double bw_gather = 3.5e12;     // B/s of useful bytes when whole 128-byte lines are used
+    double t_fixed = 2.0e-6;       // s per row visit: rowptr, first index block, store
+    double t_step = 0.8e-6;        // s per dependent gather step of a group
+    double t_block = 0.6e-6;       // s per 64-nonzero index block
+    double t_launch = 6.0e-6;      // s per extra kernel launch
+    int waves = 8192;              // resident wavefronts (256 CUs x 4 SIMDs x 8)
+};
+
+double estimate_one(const Model& m, int op, int64_t n_rows, int64_t nnz, const int64_t* hist, int64_t max_deg, int32_t F,
+                    int esize, const Resolved& r)
+{
+    const double row_bytes = static_cast<double>(F) * esize;
+    const double tile_bytes = std::min<double>(row_bytes, static_cast<double>(r.f_tile) * esize);
+    const double lines = std::ceil(tile_bytes / 128.0) * 128.0;
+    const double eff = tile_bytes / lines;
+    const double vec_pen = r.mapping == MAP_PLAIN ? 0.6 : (r.vec * esize >= 16 ? 1.0 : (r.vec * esize >= 8 ? 0.9 : 0.75));
+    double t_bw = nnz * row_bytes / (m.bw_gather * eff * vec_pen);
+    if (op == AUTOSAGE_OP_SPMM) t_bw += (8.0 * nnz * r.tiles + 4.0 * n_rows + 4.0 * n_rows * F) / m.bw_stream;
+    else t_bw += (8.0 * nnz + 4.0 * n_rows + row_bytes * n_rows) / m.bw_stream;
+
+    const int G = r.G * r.HW;
+    const int S = 64 / G;
+    const int U = r.unroll;
+    double wave_time = 0.0;          // summed over all wavefront visits
+    double longest = 0.0;
+    int64_t hub_nnz = 0, hub_rows = 0;
+    for (int b = 0; b < 33; ++b) {
+        if (hist[b] == 0) continue;
+        const double lo = b == 0 ? 0.0 : std::ldexp(1.0, b - 1);
+        double deg = b == 0 ? 0.0 : std::min<double>(1.5 * lo, static_cast<double>(max_deg));
+        if (r.hub_t > 0 && lo >= r.hub_t) {
+            hub_nnz += static_cast<int64_t>(deg * hist[b]);
+            hub_rows += hist[b];
+            continue;
+        }
+        double steps, blocks;
+        if (r.mapping == MAP_MULTI_ROW) {
+            steps = std::ceil(deg / U);
+            blocks = 0.0;
+        } else if (r.mapping == MAP_PLAIN) {
+            steps = deg * 0.5;           // one nonzero at a time, partly overlapped by the hardware
+            blocks = 0.0;
+        } else {
+            steps = std::ceil(deg / (S * U));
+            blocks = std::ceil(deg / 64.0);
+        }
+        const double t_row = m.t_fixed + steps * m.t_step + blocks * m.t_block;
+        const double visits = r.mapping == MAP_MULTI_ROW ? static_cast<double>(hist[b]) / S * (1.0 + 0.25 * std::log2((double)S))
+                                                         : static_cast<double>(hist[b]);
+        wave_time += visits * t_row * r.tiles;
+        longest = std::max(longest, t_row);
+    }
+    double t_lat = wave_time / m.waves;
+    double t = std::max(std::max(t_bw, t_lat), longest);
+    if (r.hub_t > 0) {
+        const double chunks = static_cast<double>(hub_nnz) / r.hub_chunk + hub_rows;
+        t += 3 * m.t_launch + (op == AUTOSAGE_OP_SPMM ? 2.0 * chunks * F * 4.0 / m.bw_stream + m.t_launch : 0.0);
+        const double chunk_steps = std::ceil(static_cast<double>(r.hub_chunk) / (r.wpg * S * U));
+        t = std::max(t, m.t_fixed + chunk_steps * m.t_step);
+    }
+    return t;
+}
+
+}  // namespace
+
+void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, int64_t nnz, const int64_t* hist33,
+               int64_t max_deg, int32_t F, int dt, int align_bytes, std::vector<autosage_schedule_t>* out,
+               std::vector<double>* est)
+{
+    (void)n_cols;
+    Model m;
+    if (h && h->cu_count > 0) m.waves = h->cu_count * 32;
+    const int esize = dt == DT_BF16 ? 2 : 4;
+    const Params dflt;
+    const Params& p = h ? h->params : dflt;
+    std::vector<std::pair<double, autosage_schedule_t>> all;
+    const int hubs[] = {0, 512, 1024, 2048, 4096};
+    const int unrolls[] = {4, 8, 2};
+    for (int mapping = AUTOSAGE_MAP_WAVE_ROW; mapping <= AUTOSAGE_MAP_MULTI_ROW; ++mapping) {
+        for (int vb = 16; vb >= esize; vb >>= 1) {
+            for (int u : unrolls) {
+                for (int hub : hubs) {
+                    if (hub > 0 && max_deg < hub) continue;
+                    if (p.force_hub_t >= 0 && hub != hubs[0]) continue;   // forced value handled below
+                    for (int xcd = 0; xcd <= 1; ++xcd) {
+                        autosage_schedule_t s{};
+                        s.mapping = mapping;
+                        s.f_tile = p.force_ftile > 0 ? p.force_ftile : 0;
+                        s.waves_per_wg = p.force_wpb > 0 ? p.force_wpb : 4;
+                        s.vec_bytes = vb;
+                        s.unroll = u;
+                        s.hub_t = p.force_hub_t >= 0 ? p.force_hub_t : hub;
+                        s.hub_chunk = s.hub_t;
+                        s.xcd_remap = xcd;
+                        Resolved r;
+                        if (resolve_schedule(s, op, F, dt, 1, align_bytes, align_bytes, &r) != AUTOSAGE_OK) continue;
+                        if (r.unroll != u) continue;
+                        double t = estimate_one(m, op, n_rows, nnz, hist33, max_deg, F, esize, r);
+                        if (xcd) t *= 1.001;      // no locality information in the histogram: keep it next to its twin
+                        // schedules that resolve to the same kernel shape under a smaller unroll are duplicates
+                        if ((r.K == 2 && u == 8) || (r.K > 2 && r.K <= 4 && u > 2) || (r.K > 4 && u > 2)) continue;
+                        all.emplace_back(t, s);
+                    }
+                }
+            }
+        }
+    }
+    std::stable_sort(all.begin(), all.end(), [](const auto& a, const auto& b) { return a.first < b.first; });
+    out->clear();
+    est->clear();
+    for (const auto& e : all) {
+        out->push_back(e.second);
+        est->push_back(e.first);
+    }
+}
+
+}  // namespace autosage
+
+// ------------------------------------------------------------------------------------------
+// C ABI: host-only pieces
+// ------------------------------------------------------------------------------------------
+extern "C" autosage_status_t autosage_decide_from_times(int32_t n_cand, const double* t_cand, double t_baseline,
+                                                        double alpha, int32_t* choice)
+{
+    if (n_cand < 0 || (n_cand > 0 && !t_cand) || !choice) return AUTOSAGE_ERR_INVALID_ARG;
+    *choice = decide_from_times(n_cand, t_cand, t_baseline, alpha);
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_shortlist(autosage_handle_t h, autosage_op_t op, int64_t n_rows, int64_t n_cols,
+                                                int64_t nnz, const int64_t* hist33, int64_t max_deg, int32_t F,
+                                                autosage_dtype_t dt, int32_t align_bytes, autosage_schedule_t* out,
+                                                double* est_seconds, int32_t max_out, int32_t* n_out)
+{
+    if (!h || !hist33 || !n_out || max_out < 0 || (max_out > 0 && !out) || F <= 0 || n_rows < 0 || nnz < 0)
+        return AUTOSAGE_ERR_INVALID_ARG;
+    if (op != AUTOSAGE_OP_SPMM && op != AUTOSAGE_OP_SDDMM) return AUTOSAGE_ERR_INVALID_ARG;
+    if (align_bytes < 1 || (align_bytes & (align_bytes - 1)) != 0) return AUTOSAGE_ERR_INVALID_ARG;
+    std::vector<autosage_schedule_t> c;
+    std::vector<double> e;
+    shortlist(h, op, n_rows, n_cols, nnz, hist33, max_deg, F, dt, align_bytes > 16 ? 16 : align_bytes, &c, &e);
+    const int n = std::min<int>(max_out, (int)c.size());
+    for (int i = 0; i < n; ++i) {
+        out[i] = c[i];
+        if (est_seconds) est_seconds[i] = e[i];
+    }
+    *n_out = n;
+    return AUTOSAGE_OK;
+}
+
+// ---- cache ---------------------------------------------------------------------------------
+extern "C" autosage_status_t autosage_cache_clear(autosage_handle_t h)
+{
+    if (!h) return AUTOSAGE_ERR_INVALID_ARG;
+    h->cache.clear();
+    h->memo.clear();
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_cache_lookup(autosage_handle_t h, uint64_t graph_sig, int32_t F, autosage_op_t op,
+                                                   autosage_dtype_t dt, autosage_schedule_t* sched, int32_t* found)
+{
+    if (!h || !found) return AUTOSAGE_ERR_INVALID_ARG;
+    auto it = h->cache.find(CacheKey{graph_sig, F, (int32_t)op, (int32_t)dt});
+    *found = it != h->cache.end();
+    if (*found && sched) *sched = it->second.sched;
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_cache_insert(autosage_handle_t h, uint64_t graph_sig, int32_t F, autosage_op_t op,
+                                                   autosage_dtype_t dt, const autosage_schedule_t* sched)
+{
+    if (!h || !sched) return AUTOSAGE_ERR_INVALID_ARG;
+    h->cache[CacheKey{graph_sig, F, (int32_t)op, (int32_t)dt}] = CacheEntry{*sched, 0.0, 0.0};
+    return AUTOSAGE_OK;
+}
+
+// One record per line:
+//   autosage-cache-v1 <device_sig> <graph_sig hex> <F> <op> <dt> <mapping> <f_tile> <wpg> <vec_bytes> <unroll>
+//   <hub_t> <hub_chunk> <xcd_remap> <t_baseline_ms> <t_chosen_ms>
+// Records of another device signature are kept out of the in-memory cache (stale-reuse guard).
+extern "C" autosage_status_t autosage_cache_load(autosage_handle_t h, const char* path)
+{
+    if (!h || !path) return AUTOSAGE_ERR_INVALID_ARG;
+    std::ifstream in(path);
+    if (!in) return AUTOSAGE_ERR_IO;
+    std::string line;
+    while (std::getline(in, line)) {
+        std::istringstream ss(line);
+        std::string tag, dev, sig_hex;
+        CacheKey k{};
+        CacheEntry e{};
+        autosage_schedule_t& s = e.sched;
+        if (!(ss >> tag >> dev >> sig_hex >> k.F >> k.op >> k.dt >> s.mapping >> s.f_tile >> s.waves_per_wg >> s.vec_bytes >>
+              s.unroll >> s.hub_t >> s.hub_chunk >> s.xcd_remap >> e.t_baseline_ms >> e.t_chosen_ms))
+            continue;
+        if (tag != "autosage-cache-v1" || dev != h->device_sig) continue;
+        char* end = nullptr;
+        k.graph_sig = std::strtoull(sig_hex.c_str(), &end, 16);
+        if (end == sig_hex.c_str() || *end != '\0') continue;
+        if (s.mapping < 0 || s.mapping > 2 || k.op < 0 || k.op > 3 || k.dt < 0 || k.dt > 1 || k.F <= 0) continue;
+        h->cache[k] = e;
+    }
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_cache_save(autosage_handle_t h, const char* path)
+{
+    if (!h || !path) return AUTOSAGE_ERR_INVALID_ARG;
+    const std::string tmp = std::string(path) + ".tmp";
+    {
+        std::ofstream out(tmp, std::ios::trunc);
+        if (!out) return AUTOSAGE_ERR_IO;
+        for (const auto& kv : h->cache) {
+            const CacheKey& k = kv.first;
+            const autosage_schedule_t& s = kv.second.sched;
+            char buf[512];
+            std::snprintf(buf, sizeof buf, "autosage-cache-v1 %s %016llx %d %d %d %d %d %d %d %d %d %d %d %.6f %.6f\n",
+                          h->device_sig.c_str(), (unsigned long long)k.graph_sig, k.F, k.op, k.dt, s.mapping, s.f_tile,
+                          s.waves_per_wg, s.vec_bytes, s.unroll, s.hub_t, s.hub_chunk, s.xcd_remap,
+                          kv.second.t_baseline_ms, kv.second.t_chosen_ms);
+            out << buf;
+        }
+        out.flush();
+        if (!out) return AUTOSAGE_ERR_IO;
+    }
+    if (std::rename(tmp.c_str(), path) != 0) return AUTOSAGE_ERR_IO;
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_last_decision(autosage_handle_t h, char* json_buf, size_t n)
+{
+    if (!h || !json_buf || n == 0) return AUTOSAGE_ERR_INVALID_ARG;
+    const size_t m = std::min(n - 1, h->last_decision.size());
+    std::memcpy(json_buf, h->last_decision.data(), m);
+    json_buf[m] = '\0';
+    return AUTOSAGE_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// the full decision
+// ------------------------------------------------------------------------------------------
+namespace {
+
+struct OpInput {
+    int op;
+    int64_t n_rows, n_cols, nnz;
+    const int32_t* rowptr;
+    const int32_t* colind;
+    const float* val;
+    const void* d0;
+    int64_t ld0;
+    const void* d1;
+    int64_t ld1;
+    float* out;
+    int64_t ld_out;
+    int32_t F;
+    int dt;
+};
+
+autosage_status_t run_once(const OpInput& in, const RowMap& rows, const autosage_schedule_t& s, void* ws, size_t ws_bytes,
+                           hipStream_t st)
+{
+    const int esize = in.dt == DT_BF16 ? 2 : 4;
+    Resolved r;
+    if (in.op == AUTOSAGE_OP_SPMM) {
+        autosage_status_t rc = resolve_schedule(s, in.op, in.F, in.dt, 1, common_alignment(in.d0, in.ld0, esize),
+                                                common_alignment(in.out, in.ld_out, 4), &r);
+        if (rc != AUTOSAGE_OK) return rc;
+        SpmmArgs a{};
+        a.rows = rows;
+        a.rowptr = in.rowptr;
+        a.colind = in.colind;
+        a.val = in.val;
+        a.B = in.d0;
+        a.ldb = in.ld0;
+        a.C = in.out;
+        a.ldc = in.ld_out;
+        a.F = in.F;
+        a.dt = in.dt;
+        a.heads = 1;
+        a.head_dim = in.F;
+        return exec_spmm(a, r, in.nnz, ws, ws_bytes, st);
+    }
+    int al = common_alignment(in.d0, in.ld0, esize);
+    const int al2 = common_alignment(in.d1, in.ld1, esize);
+    if (al2 < al) al = al2;
+    autosage_status_t rc = resolve_schedule(s, in.op, in.F, in.dt, 1, al, 16, &r);
+    if (rc != AUTOSAGE_OK) return rc;
+    SddmmArgs a{};
+    a.rows = rows;
+    a.rowptr = in.rowptr;
+    a.colind = in.colind;
+    a.X = in.d0;
+    a.ldx = in.ld0;
+    a.Y = in.d1;
+    a.ldy = in.ld1;
+    a.out = in.out;
+    a.F = in.F;
+    a.dt = in.dt;
+    a.heads = 1;
+    a.scale = 1.0f;
+    return exec_sddmm(a, r, in.nnz, ws, ws_bytes, st);
+}
+
+// Median of up to `iters` timed runs (one untimed warm-up first); stops early once the timed
+// runs add up to cap_ms.  Returns +inf when the schedule cannot run on this input.
+double time_schedule(autosage_ctx* h, const OpInput& in, const RowMap& rows, const autosage_schedule_t& s, void* ws,
+                     size_t ws_bytes, hipStream_t st, int iters, double cap_ms)
+{
+    const double inf = std::numeric_limits<double>::infinity();
+    if (run_once(in, rows, s, ws, ws_bytes, st) != AUTOSAGE_OK) return inf;
+    if (hipStreamSynchronize(st) != hipSuccess) return inf;
+    std::vector<double> t;
+    double total = 0.0;
+    for (int i = 0; i < iters; ++i) {
+        if (hipEventRecord(h->ev0, st) != hipSuccess) return inf;
+        if (run_once(in, rows, s, ws, ws_bytes, st) != AUTOSAGE_OK) return inf;
+        if (hipEventRecord(h->ev1, st) != hipSuccess) return inf;
+        if (hipEventSynchronize(h->ev1) != hipSuccess) return inf;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, h->ev0, h->ev1) != hipSuccess) return inf;
+        t.push_back(ms);
+        total += ms;
+        if (total >= cap_ms) break;
+    }
+    std::sort(t.begin(), t.end());
+    return t[t.size() / 2];
+}
+
+std::string num(double x)
+{
+    if (!std::isfinite(x)) return "null";
+    char b[64];
+    std::snprintf(b, sizeof b, "%.6f", x);
+    return b;
+}
+
+}  // namespace
+
+extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t op, int64_t n_rows, int64_t n_cols,
+                                             int64_t nnz, const int32_t* rowptr, const int32_t* colind, const float* val,
+                                             const void* dense0, int64_t ld0, const void* dense1, int64_t ld1,
+                                             float* out, int64_t ld_out, int32_t F, autosage_dtype_t dt,
+                                             void* workspace, size_t workspace_bytes, void* stream,
+                                             autosage_schedule_t* chosen)
+{
+    if (!h || !chosen || !rowptr || F <= 0 || n_rows < 0 || nnz < 0) return AUTOSAGE_ERR_INVALID_ARG;
+    if (op != AUTOSAGE_OP_SPMM && op != AUTOSAGE_OP_SDDMM) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (nnz > 0 && (!colind || !dense0 || !out || (op == AUTOSAGE_OP_SPMM && !val) || (op == AUTOSAGE_OP_SDDMM && !dense1)))
+        return AUTOSAGE_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const auto wall0 = std::chrono::steady_clock::now();
+
+    // 1. features and signature (memoised per rowptr pointer when allowed)
+    int64_t hist[33];
+    int64_t max_deg = 0;
+    uint64_t sig = 0;
+    bool have = false;
+    if (h->params.memoize_signature) {
+        for (const SigMemo& m : h->memo) {
+            if (m.rowptr == rowptr && m.n_rows == n_rows && m.n_cols == n_cols && m.nnz == nnz) {
+                sig = m.sig;
+                max_deg = m.max_deg;
+                std::memcpy(hist, m.hist, sizeof hist);
+                have = true;
+                break;
+            }
+        }
+    }
+    if (!have) {
+        int64_t nnz_dev = 0;
+        autosage_status_t rc = autosage_graph_features(h, n_rows, n_cols, rowptr, hist, &max_deg, &nnz_dev, &sig, stream);
+        if (rc != AUTOSAGE_OK) return rc;
+        if (nnz_dev != nnz) return AUTOSAGE_ERR_INVALID_ARG;
+        if (h->params.memoize_signature) {
+            SigMemo m{};
+            m.rowptr = rowptr;
+            m.n_rows = n_rows;
+            m.n_cols = n_cols;
+            m.nnz = nnz;
+            m.sig = sig;
+            m.max_deg = max_deg;
+            std::memcpy(m.hist, hist, sizeof hist);
+            if (h->memo.size() >= 16) h->memo.erase(h->memo.begin());
+            h->memo.push_back(m);
+        }
+    }
+
+    std::ostringstream js;
+    char sigbuf[32];
+    std::snprintf(sigbuf, sizeof sigbuf, "%016llx", (unsigned long long)sig);
+    js << "{\"op\":" << (int)op << ",\"F\":" << F << ",\"dt\":" << (int)dt << ",\"graph_sig\":\"" << sigbuf
+       << "\",\"device_sig\":\"" << h->device_sig << "\",\"alpha\":" << num(h->params.alpha);
+
+    // 2. cache
+    const CacheKey key{sig, F, (int32_t)op, (int32_t)dt};
+    auto it = h->cache.find(key);
+    if (it != h->cache.end()) {
+        *chosen = it->second.sched;
+        js << ",\"cache_hit\":true,\"replay_miss\":false,\"choice\":" << schedule_json(*chosen) << "}";
+        h->last_decision = js.str();
+        return AUTOSAGE_OK;
+    }
+    const autosage_schedule_t base = baseline_schedule();
+    if (h->params.replay_only) {
+        *chosen = base;
+        js << ",\"cache_hit\":false,\"replay_miss\":true,\"choice\":" << schedule_json(base) << "}";
+        h->last_decision = js.str();
+        return AUTOSAGE_OK;
+    }
+
+    // 3. shortlist
+    const int esize = dt == AUTOSAGE_BF16 ? 2 : 4;
+    int al = common_alignment(dense0, ld0, esize);
+    if (op == AUTOSAGE_OP_SDDMM) al = std::min(al, common_alignment(dense1, ld1, esize));
+    else al = std::min(al, common_alignment(out, ld_out, 4));
+    std::vector<autosage_schedule_t> cands;
+    std::vector<double> est;
+    shortlist(h, op, n_rows, n_cols, nnz, hist, max_deg, F, dt, al, &cands, &est);
+    const int topk = std::max(0, std::min<int>(h->params.probe_topk, (int)cands.size()));
+
+    // 4. probes on a strided row sample (all candidates see the identical sample)
+    int64_t stride = (int64_t)std::floor(1.0 / h->params.probe_frac);
+    if (stride < 1) stride = 1;
+    const int64_t min_rows = std::max(1, h->params.probe_min_rows);
+    if (n_rows / stride < min_rows) stride = std::max<int64_t>(1, n_rows / min_rows);
+    RowMap sample{(int32_t)(stride / 2), (int32_t)stride, 0};
+    sample.count = n_rows > sample.first ? (int32_t)((n_rows - sample.first + stride - 1) / stride) : 0;
+    OpInput in{(int)op, n_rows, n_cols, nnz, rowptr, colind, val, dense0, ld0, dense1, ld1, out, ld_out, F, (int)dt};
+
+    const double tb = time_schedule(h, in, sample, base, workspace, workspace_bytes, st, h->params.probe_iters,
+                                    h->params.probe_cap_ms);
+    if (!std::isfinite(tb)) return AUTOSAGE_ERR_HIP;
+    std::vector<double> tc(topk);
+    js << ",\"cache_hit\":false,\"replay_miss\":false,\"probe_rows\":" << sample.count << ",\"probe_stride\":" << stride
+       << ",\"t_baseline_ms\":" << num(tb) << ",\"candidates\":[";
+    for (int c = 0; c < topk; ++c) {
+        tc[c] = time_schedule(h, in, sample, cands[c], workspace, workspace_bytes, st, h->params.probe_iters,
+                              h->params.probe_cap_ms);
+        js << (c ? "," : "") << "{\"sched\":" << schedule_json(cands[c]) << ",\"est_ms\":" << num(est[c] * 1e3)
+           << ",\"t_ms\":" << num(tc[c]) << "}";
+    }
+    js << "]";
+
+    // 5. guardrail
+    int choice = decide_from_times(topk, tc.data(), tb, h->params.alpha);
+    double t_choice = choice >= 0 ? tc[choice] : tb;
+    js << ",\"choice_index\":" << choice;
+
+    // 6. the guardrail speaks about the sample; confirm once on the whole input
+    if (choice >= 0 && h->params.confirm_full) {
+        const RowMap full{0, 1, (int32_t)n_rows};
+        const double cap = std::numeric_limits<double>::infinity();
+        const double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, cap);
+        const double tf_b = time_schedule(h, in, full, base, workspace, workspace_bytes, st, 2, cap);
+        const bool demote = !(tf_c <= tf_b);
+        js << ",\"confirm\":{\"t_choice_ms\":" << num(tf_c) << ",\"t_baseline_ms\":" << num(tf_b) << ",\"demoted\":"
+           << (demote ? "true" : "false") << "}";
+        if (demote) {
+            choice = -1;
+            t_choice = tb;
+        }
+    }
+    *chosen = choice >= 0 ? cands[choice] : base;
+    h->cache[key] = CacheEntry{*chosen, tb, t_choice};
+    const double wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - wall0).count();
+    js << ",\"choice\":" << schedule_json(*chosen) << ",\"probe_wall_ms\":" << num(wall_ms) << "}";
+    h->last_decision = js.str();
+    return AUTOSAGE_OK;
+}
