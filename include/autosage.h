@@ -224,6 +224,14 @@ autosage_status_t autosage_cache_lookup(autosage_handle_t h, uint64_t graph_sig,
 autosage_status_t autosage_cache_insert(autosage_handle_t h, uint64_t graph_sig, int32_t F, autosage_op_t op,
                                         autosage_dtype_t dt, const autosage_schedule_t* sched);
 
+/* Telemetry (Contributions: deployment toggles and telemetry).  Between profile_begin and
+ * profile_read every kernel stage the handle launches is bracketed by a pair of HIP events on its
+ * stream.  profile_read waits for the recorded stages, writes JSON {"stage":{"calls":n,"total_ms":t},...}
+ * (stage names: hub_partition, spmm_rows, spmm_hub, sddmm_rows, sddmm_hub, softmax_rows, softmax_hub,
+ * attn_sddmm_rows, attn_sddmm_hub, attn_spmm_rows, attn_spmm_hub) and switches profiling off. */
+autosage_status_t autosage_profile_begin(autosage_handle_t h);
+autosage_status_t autosage_profile_read(autosage_handle_t h, char* json_buf, size_t n);
+
 /* The baseline (fallback) schedule of the guardrail: plain one-wavefront-per-row kernel. */
 autosage_status_t autosage_baseline_schedule(autosage_schedule_t* out);
 

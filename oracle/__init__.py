@@ -106,14 +106,15 @@ def row_softmax(rowptr, s) -> np.ndarray:
 
 
 def csr_attention(rowptr, colind, Q, K, V, scale, return_scores: bool = False):
-    """O = softmax_row(scale * SDDMM(Q, K)) V on the pattern; Q, K, V are [N, H, d]."""
+    """O = softmax_row(scale * SDDMM(Q, K)) V on the pattern; Q is [n_rows, H, d], K and V are [n_cols, H, d]."""
     lib = _load()
     rowptr, colind = _i32(rowptr), _i32(colind)
     Q, dt = _dense(Q)
     K, dt2 = _dense(K)
     V, dt3 = _dense(V)
-    assert dt == dt2 == dt3 and Q.ndim == 3
+    assert dt == dt2 == dt3 and Q.ndim == 3 and K.shape == V.shape and K.shape[1:] == Q.shape[1:]
     N, H, d = Q.shape
+    assert colind.size == 0 or int(colind.max()) < K.shape[0]
     assert rowptr.shape[0] == N + 1
     nnz = int(rowptr[-1])
     O = np.zeros((N, H, d), dtype=np.float64)

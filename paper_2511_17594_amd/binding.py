@@ -71,6 +71,8 @@ def _load():
         "autosage_cache_lookup": [vp, c.c_uint64, i32, c.c_int, c.c_int, sp, c.POINTER(i32)],
         "autosage_cache_insert": [vp, c.c_uint64, i32, c.c_int, c.c_int, sp],
         "autosage_baseline_schedule": [sp],
+        "autosage_profile_begin": [vp],
+        "autosage_profile_read": [vp, c.c_char_p, sz],
     }
     for name, args in sigs.items():
         fn = getattr(lib, name)          # raises AttributeError if the library lacks a declared symbol
@@ -250,6 +252,14 @@ class Handle:
     def last_decision(self) -> dict:
         buf = ctypes.create_string_buffer(1 << 16)
         _check(_lib.autosage_last_decision(self._h, buf, len(buf)), "autosage_last_decision")
+        return json.loads(buf.value.decode())
+
+    def profile_begin(self):
+        _check(_lib.autosage_profile_begin(self._h), "autosage_profile_begin")
+
+    def profile_read(self) -> dict:
+        buf = ctypes.create_string_buffer(1 << 14)
+        _check(_lib.autosage_profile_read(self._h, buf, len(buf)), "autosage_profile_read")
         return json.loads(buf.value.decode())
 
     def cache_load(self, path: str):

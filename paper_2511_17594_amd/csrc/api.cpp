@@ -114,6 +114,18 @@ autosage_status_t resolve_schedule(const autosage_schedule_t& s, int op, int32_t
         r.K = 1;
         r.f_tile = 64;
         r.tiles = (F + 63) / 64;
+        if (r.hub_t > 0) {
+            // the plain kernel only serves the light rows; hub chunks run the wavefront-per-row shape
+            autosage_schedule_t hub = s;
+            hub.mapping = AUTOSAGE_MAP_WAVE_ROW;
+            hub.vec_bytes = 0;
+            hub.f_tile = 0;
+            Resolved hr;
+            autosage_status_t rc = resolve_schedule(hub, op, F, dt, heads, align_in, align_out, &hr);
+            if (rc != AUTOSAGE_OK) return rc;
+            hr.mapping = AUTOSAGE_MAP_PLAIN;
+            r = hr;
+        }
         *out = r;
         return AUTOSAGE_OK;
     }
@@ -220,7 +232,33 @@ bool carve_hub(void* ws, size_t ws_bytes, int64_t count, int64_t nnz, int hub_t,
     return true;
 }
 
-autosage_status_t exec_spmm(const SpmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes, hipStream_t st)
+StageTimer::StageTimer(autosage_ctx* h, const char* stage, hipStream_t st) : h_(h), st_(st)
+{
+    if (!h_ || !h_->profiling) return;
+    if (h_->spans_used == h_->spans.size()) {
+        autosage_ctx::StageSpan s{stage, nullptr, nullptr};
+        if (hipEventCreate(&s.start) != hipSuccess || hipEventCreate(&s.stop) != hipSuccess) return;
+        h_->spans.push_back(s);
+    }
+    autosage_ctx::StageSpan& s = h_->spans[h_->spans_used++];
+    s.stage = stage;
+    hipEventRecord(s.start, st_);
+    stop_ = s.stop;
+}
+
+StageTimer::~StageTimer()
+{
+    if (stop_) hipEventRecord(stop_, st_);
+}
+
+#define STAGE(h, name, st, call)      \
+    do {                              \
+        StageTimer timer__(h, name, st); \
+        HIP_TRY(call);                \
+    } while (0)
+
+autosage_status_t exec_spmm(autosage_ctx* h, const SpmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes,
+                            hipStream_t st)
 {
     if (a.rows.count == 0) return AUTOSAGE_OK;
     HubMeta meta{};
@@ -228,24 +266,25 @@ autosage_status_t exec_spmm(const SpmmArgs& a, const Resolved& r, int64_t nnz, v
     if (r.hub_t > 0) {
         if (!carve_hub(ws, ws_bytes, a.rows.count, nnz, r.hub_t, r.hub_chunk, a.F, &meta, &part, nullptr))
             return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
-        HIP_TRY(launch_hub_partition(a.rows, a.rowptr, r.hub_t, r.hub_chunk, meta, st));
+        STAGE(h, "hub_partition", st, launch_hub_partition(a.rows, a.rowptr, r.hub_t, r.hub_chunk, meta, st));
     }
-    HIP_TRY(launch_spmm_rows(a, r, st));
-    if (r.hub_t > 0) HIP_TRY(launch_spmm_hub(a, r, meta, part, st));
+    STAGE(h, "spmm_rows", st, launch_spmm_rows(a, r, st));
+    if (r.hub_t > 0) STAGE(h, "spmm_hub", st, launch_spmm_hub(a, r, meta, part, st));
     return AUTOSAGE_OK;
 }
 
-autosage_status_t exec_sddmm(const SddmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes, hipStream_t st)
+autosage_status_t exec_sddmm(autosage_ctx* h, const SddmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes,
+                             hipStream_t st)
 {
     if (a.rows.count == 0) return AUTOSAGE_OK;
     HubMeta meta{};
     if (r.hub_t > 0) {
         if (!carve_hub(ws, ws_bytes, a.rows.count, nnz, r.hub_t, r.hub_chunk, 0, &meta, nullptr, nullptr))
             return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
-        HIP_TRY(launch_hub_partition(a.rows, a.rowptr, r.hub_t, r.hub_chunk, meta, st));
+        STAGE(h, "hub_partition", st, launch_hub_partition(a.rows, a.rowptr, r.hub_t, r.hub_chunk, meta, st));
     }
-    HIP_TRY(launch_sddmm_rows(a, r, st));
-    if (r.hub_t > 0) HIP_TRY(launch_sddmm_hub(a, r, meta, st));
+    STAGE(h, "sddmm_rows", st, launch_sddmm_rows(a, r, st));
+    if (r.hub_t > 0) STAGE(h, "sddmm_hub", st, launch_sddmm_hub(a, r, meta, st));
     return AUTOSAGE_OK;
 }
 
@@ -321,6 +360,10 @@ extern "C" autosage_status_t autosage_destroy(autosage_handle_t h)
     if (h->dev_flag) hipFree(h->dev_flag);
     if (h->ev0) hipEventDestroy(h->ev0);
     if (h->ev1) hipEventDestroy(h->ev1);
+    for (auto& s : h->spans) {
+        if (s.start) hipEventDestroy(s.start);
+        if (s.stop) hipEventDestroy(s.stop);
+    }
     delete h;
     return st;
 }
@@ -446,7 +489,7 @@ extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, 
     a.dt = dt;
     a.heads = 1;
     a.head_dim = F;
-    return exec_spmm(a, r, nnz, workspace, workspace_bytes, st);
+    return exec_spmm(h, a, r, nnz, workspace, workspace_bytes, st);
 }
 
 extern "C" autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
@@ -489,10 +532,10 @@ extern "C" autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows,
     a.dt = dt;
     a.heads = 1;
     a.scale = 1.0f;
-    return exec_sddmm(a, r, nnz, workspace, workspace_bytes, st);
+    return exec_sddmm(h, a, r, nnz, workspace, workspace_bytes, st);
 }
 
-static autosage_status_t exec_softmax(const SoftmaxArgs& a, int64_t nnz, int hub_t, int hub_chunk, int wpg,
+static autosage_status_t exec_softmax(autosage_ctx* h, const SoftmaxArgs& a, int64_t nnz, int hub_t, int hub_chunk, int wpg,
                                       const HubMeta* shared_meta, float* shared_part, void* ws, size_t ws_bytes,
                                       hipStream_t st)
 {
@@ -506,11 +549,11 @@ static autosage_status_t exec_softmax(const SoftmaxArgs& a, int64_t nnz, int hub
         } else {
             if (!carve_hub(ws, ws_bytes, a.rows.count, nnz, hub_t, hub_chunk, 2 * (int64_t)a.H, &meta, &part, nullptr))
                 return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
-            HIP_TRY(launch_hub_partition(a.rows, a.rowptr, hub_t, hub_chunk, meta, st));
+            STAGE(h, "hub_partition", st, launch_hub_partition(a.rows, a.rowptr, hub_t, hub_chunk, meta, st));
         }
     }
-    HIP_TRY(launch_softmax_rows(a, hub_t, wpg, st));
-    if (hub_t > 0) HIP_TRY(launch_softmax_hub(a, hub_chunk, meta, part, st));
+    STAGE(h, "softmax_rows", st, launch_softmax_rows(a, hub_t, wpg, st));
+    if (hub_t > 0) STAGE(h, "softmax_hub", st, launch_softmax_hub(a, hub_chunk, meta, part, st));
     return AUTOSAGE_OK;
 }
 
@@ -532,7 +575,7 @@ extern "C" autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64
     a.in = in;
     a.out = out;
     a.H = H;
-    return exec_softmax(a, nnz, hub_t, chunk, 4, nullptr, nullptr, workspace, workspace_bytes,
+    return exec_softmax(h, a, nnz, hub_t, chunk, 4, nullptr, nullptr, workspace, workspace_bytes,
                         static_cast<hipStream_t>(stream));
 }
 
@@ -593,7 +636,7 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
         if (!carve_hub(hub_ws, hub_ws_bytes, N, nnz, rs.hub_t, rs.hub_chunk, (int64_t)attention_part_floats(H, d), &meta,
                        &part, nullptr))
             return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
-        HIP_TRY(launch_hub_partition(rows, rowptr, rs.hub_t, rs.hub_chunk, meta, st));
+        STAGE(h, "hub_partition", st, launch_hub_partition(rows, rowptr, rs.hub_t, rs.hub_chunk, meta, st));
     }
     // stage 1: scores
     SddmmArgs sa{};
@@ -610,8 +653,8 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
     sa.heads = H;
     sa.scale = scale;
     if (nnz > 0) {
-        HIP_TRY(launch_sddmm_rows(sa, rs, st));
-        if (rs.hub_t > 0) HIP_TRY(launch_sddmm_hub(sa, rs, meta, st));
+        STAGE(h, "attn_sddmm_rows", st, launch_sddmm_rows(sa, rs, st));
+        if (rs.hub_t > 0) STAGE(h, "attn_sddmm_hub", st, launch_sddmm_hub(sa, rs, meta, st));
     }
     // stage 2: row-softmax in place
     SoftmaxArgs ma{};
@@ -620,7 +663,7 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
     ma.in = S;
     ma.out = S;
     ma.H = H;
-    rc = exec_softmax(ma, nnz, rs.hub_t, rs.hub_chunk, rs.wpg, rs.hub_t > 0 ? &meta : nullptr, part, nullptr, 0, st);
+    rc = exec_softmax(h, ma, nnz, rs.hub_t, rs.hub_chunk, rs.wpg, rs.hub_t > 0 ? &meta : nullptr, part, nullptr, 0, st);
     if (rc != AUTOSAGE_OK) return rc;
     // stage 3: weighted sum of V rows with per-head weights
     SpmmArgs pa{};
@@ -636,8 +679,8 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
     pa.dt = in_dt;
     pa.heads = H > 1 ? H : 1;
     pa.head_dim = d;
-    HIP_TRY(launch_spmm_rows(pa, rp, st));
-    if (rp.hub_t > 0) HIP_TRY(launch_spmm_hub(pa, rp, meta, part, st));
+    STAGE(h, "attn_spmm_rows", st, launch_spmm_rows(pa, rp, st));
+    if (rp.hub_t > 0) STAGE(h, "attn_spmm_hub", st, launch_spmm_hub(pa, rp, meta, part, st));
     return AUTOSAGE_OK;
 }
 
@@ -732,4 +775,48 @@ extern "C" autosage_status_t autosage_validate_csr(autosage_handle_t h, int64_t 
     HIP_TRY(hipMemcpyAsync(&flag, h->dev_flag, sizeof flag, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     return flag ? AUTOSAGE_ERR_INVALID_ARG : AUTOSAGE_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// telemetry
+// ------------------------------------------------------------------------------------------
+extern "C" autosage_status_t autosage_profile_begin(autosage_handle_t h)
+{
+    if (!h) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    h->profiling = true;
+    h->spans_used = 0;
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_profile_read(autosage_handle_t h, char* json_buf, size_t n)
+{
+    if (!h || !json_buf || n == 0) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    h->profiling = false;
+    std::map<std::string, std::pair<int, double>> agg;
+    for (size_t i = 0; i < h->spans_used; ++i) {
+        autosage_ctx::StageSpan& s = h->spans[i];
+        HIP_TRY(hipEventSynchronize(s.stop));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, s.start, s.stop));
+        auto& e = agg[s.stage];
+        e.first += 1;
+        e.second += ms;
+    }
+    h->spans_used = 0;
+    std::string js = "{";
+    bool first = true;
+    for (const auto& kv : agg) {
+        char buf[256];
+        std::snprintf(buf, sizeof buf, "%s\"%s\":{\"calls\":%d,\"total_ms\":%.6f}", first ? "" : ",", kv.first.c_str(),
+                      kv.second.first, kv.second.second);
+        js += buf;
+        first = false;
+    }
+    js += "}";
+    const size_t m = js.size() < n - 1 ? js.size() : n - 1;
+    std::memcpy(json_buf, js.data(), m);
+    json_buf[m] = '\0';
+    return AUTOSAGE_OK;
 }

@@ -71,6 +71,14 @@ struct autosage_ctx {
     int64_t* host_features = nullptr;      // pinned mirror
     int32_t* dev_flag = nullptr;
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    // per-stage telemetry (autosage_profile_begin / autosage_profile_read)
+    bool profiling = false;
+    struct StageSpan {
+        const char* stage;
+        hipEvent_t start, stop;
+    };
+    std::vector<StageSpan> spans;
+    size_t spans_used = 0;
 };
 
 namespace autosage {
@@ -98,8 +106,24 @@ size_t hub_workspace_bytes(int64_t count, int64_t nnz, int hub_t, int hub_chunk,
 bool carve_hub(void* ws, size_t ws_bytes, int64_t count, int64_t nnz, int hub_t, int hub_chunk,
                int64_t part_floats_per_chunk, HubMeta* meta, float** part, size_t* used);
 
-autosage_status_t exec_spmm(const SpmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes, hipStream_t st);
-autosage_status_t exec_sddmm(const SddmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes, hipStream_t st);
+autosage_status_t exec_spmm(autosage_ctx* h, const SpmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes,
+                            hipStream_t st);
+autosage_status_t exec_sddmm(autosage_ctx* h, const SddmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes,
+                             hipStream_t st);
+
+// Brackets one kernel stage with a pair of events on its stream while profiling is on.
+class StageTimer {
+public:
+    StageTimer(autosage_ctx* h, const char* stage, hipStream_t st);
+    ~StageTimer();
+    StageTimer(const StageTimer&) = delete;
+    StageTimer& operator=(const StageTimer&) = delete;
+
+private:
+    autosage_ctx* h_;
+    hipStream_t st_;
+    hipEvent_t stop_ = nullptr;
+};
 
 // Host-only selector pieces
 int decide_from_times(int n, const double* t, double tb, double alpha);

@@ -330,7 +330,7 @@ struct OpInput {
     int dt;
 };
 
-autosage_status_t run_once(const OpInput& in, const RowMap& rows, const autosage_schedule_t& s, void* ws, size_t ws_bytes,
+autosage_status_t run_once(autosage_ctx* h, const OpInput& in, const RowMap& rows, const autosage_schedule_t& s, void* ws, size_t ws_bytes,
                            hipStream_t st)
 {
     const int esize = in.dt == DT_BF16 ? 2 : 4;
@@ -352,7 +352,7 @@ autosage_status_t run_once(const OpInput& in, const RowMap& rows, const autosage
         a.dt = in.dt;
         a.heads = 1;
         a.head_dim = in.F;
-        return exec_spmm(a, r, in.nnz, ws, ws_bytes, st);
+        return exec_spmm(h, a, r, in.nnz, ws, ws_bytes, st);
     }
     int al = common_alignment(in.d0, in.ld0, esize);
     const int al2 = common_alignment(in.d1, in.ld1, esize);
@@ -372,7 +372,7 @@ autosage_status_t run_once(const OpInput& in, const RowMap& rows, const autosage
     a.dt = in.dt;
     a.heads = 1;
     a.scale = 1.0f;
-    return exec_sddmm(a, r, in.nnz, ws, ws_bytes, st);
+    return exec_sddmm(h, a, r, in.nnz, ws, ws_bytes, st);
 }
 
 // Median of up to `iters` timed runs (one untimed warm-up first); stops early once the timed
@@ -381,13 +381,13 @@ double time_schedule(autosage_ctx* h, const OpInput& in, const RowMap& rows, con
                      size_t ws_bytes, hipStream_t st, int iters, double cap_ms)
 {
     const double inf = std::numeric_limits<double>::infinity();
-    if (run_once(in, rows, s, ws, ws_bytes, st) != AUTOSAGE_OK) return inf;
+    if (run_once(h, in, rows, s, ws, ws_bytes, st) != AUTOSAGE_OK) return inf;
     if (hipStreamSynchronize(st) != hipSuccess) return inf;
     std::vector<double> t;
     double total = 0.0;
     for (int i = 0; i < iters; ++i) {
         if (hipEventRecord(h->ev0, st) != hipSuccess) return inf;
-        if (run_once(in, rows, s, ws, ws_bytes, st) != AUTOSAGE_OK) return inf;
+        if (run_once(h, in, rows, s, ws, ws_bytes, st) != AUTOSAGE_OK) return inf;
         if (hipEventRecord(h->ev1, st) != hipSuccess) return inf;
         if (hipEventSynchronize(h->ev1) != hipSuccess) return inf;
         float ms = 0.f;

@@ -100,6 +100,7 @@ def test_spmm_f32_schedules(torch, handle, ab, skew_graph, F):
     rng = np.random.default_rng(F)
     B = rng.standard_normal((A.n_cols, F)).astype(np.float32)
     ref = oracle.spmm(A.rowptr, A.colind, A.val, B)
+    ref_abs = oracle.spmm(A.rowptr, A.colind, np.abs(A.val), np.abs(B))
     ran = 0
     for kw in SCHEDULES:
         s = sched_of(ab, **kw)
@@ -109,7 +110,7 @@ def test_spmm_f32_schedules(torch, handle, ab, skew_graph, F):
             assert e.status == ab.ERR_UNSUPPORTED and kw.get("mapping") == 2, (kw, str(e))
             continue                                              # multi-row needs the row to fit 32 lanes
         ran += 1
-        err = rel_l1_rows(C, ref)
+        err = rel_l1_rows(C, ref, ref_abs)
         assert np.isfinite(C).all(), kw
         assert err.max() <= TOL_F32, (kw, F, float(err.max()), int(err.argmax()))
         assert np.all(C[A.degrees == 0] == 0.0), kw               # empty rows are exactly zero
@@ -123,6 +124,7 @@ def test_sddmm_f32_schedules(torch, handle, ab, skew_graph, F):
     X = rng.standard_normal((A.n_rows, F)).astype(np.float32)
     Y = rng.standard_normal((A.n_cols, F)).astype(np.float32)
     ref = oracle.sddmm(A.rowptr, A.colind, X, Y)
+    ref_abs = oracle.sddmm(A.rowptr, A.colind, np.abs(X), np.abs(Y))
     ran = 0
     for kw in SCHEDULES:
         s = sched_of(ab, **kw)
@@ -133,7 +135,7 @@ def test_sddmm_f32_schedules(torch, handle, ab, skew_graph, F):
             continue
         ran += 1
         assert np.isfinite(out).all(), kw
-        err = rel_l1_segments(out, ref, A.rowptr)
+        err = rel_l1_segments(out, ref, A.rowptr, ref_abs)
         assert err.max() <= TOL_F32, (kw, F, float(err.max()), int(err.argmax()))
     assert ran >= 6
 
@@ -146,6 +148,9 @@ def test_spmm_sddmm_bf16_operands(torch, handle, ab, skew_graph, F):
     X = W.float_to_bf16_bits(rng.standard_normal((A.n_rows, F)).astype(np.float32)).reshape(A.n_rows, F)
     ref_c = oracle.spmm(A.rowptr, A.colind, A.val, B)
     ref_s = oracle.sddmm(A.rowptr, A.colind, X, B)
+    absb = lambda t: (t & np.uint16(0x7FFF))                      # |x| of a bf16 bit pattern
+    abs_c = oracle.spmm(A.rowptr, A.colind, np.abs(A.val), absb(B))
+    abs_s = oracle.sddmm(A.rowptr, A.colind, absb(X), absb(B))
     for kw in (dict(mapping=0), dict(mapping=1), dict(mapping=1, hub_t=256, vec_bytes=4), dict(mapping=2, hub_t=512)):
         s = sched_of(ab, **kw)
         try:
@@ -155,8 +160,8 @@ def test_spmm_sddmm_bf16_operands(torch, handle, ab, skew_graph, F):
             assert e.status == ab.ERR_UNSUPPORTED and kw.get("mapping") == 2, (kw, str(e))
             continue
         # the bf16 inputs are exact in both paths, so only fp32 accumulation differs
-        assert rel_l1_rows(C, ref_c).max() <= TOL_F32, kw
-        assert rel_l1_segments(out, ref_s, A.rowptr).max() <= TOL_F32, kw
+        assert rel_l1_rows(C, ref_c, abs_c).max() <= TOL_F32, kw
+        assert rel_l1_segments(out, ref_s, A.rowptr, abs_s).max() <= TOL_F32, kw
 
 
 @pytest.mark.parametrize("H,hub_t", [(1, 0), (1, 128), (3, 0), (3, 64), (8, 0), (8, 256), (70, 128)])

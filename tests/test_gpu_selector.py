@@ -1,0 +1,142 @@
+"""GPU tests of the input-aware selector: probe -> guardrail -> cache -> replay, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_17594_amd import workloads as W
+from util import dev, rel_l1_rows, rel_l1_segments
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    return torch
+
+
+@pytest.fixture(scope="module")
+def ab():
+    from paper_2511_17594_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def graph():
+    return W.config2_powerlaw(n=40000, mean_deg=24.0, dmax=8192, seed=5)
+
+
+def ops(torch, ab, A, F, seed=0):
+    rng = np.random.default_rng(seed)
+    B = rng.standard_normal((A.n_cols, F)).astype(np.float32)
+    X = rng.standard_normal((A.n_rows, F)).astype(np.float32)
+    return B, X
+
+
+def timed(torch, fn, iters=7):
+    fn()
+    torch.cuda.synchronize()
+    ts = []
+    for _ in range(iters):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        e1.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    return float(np.median(ts))
+
+
+def test_decide_probe_guardrail_cache_replay(torch, ab, graph, tmp_path):
+    A, F = graph, 64
+    B, X = ops(torch, ab, A, F)
+    h = ab.Handle(0)
+    rp, ci, va, dB, dX = (dev(t, torch) for t in (A.rowptr, A.colind, A.val, B, X))
+    C = torch.empty((A.n_rows, F), dtype=torch.float32, device="cuda")
+    out = torch.empty(A.nnz, dtype=torch.float32, device="cuda")
+    ws = torch.empty(h.workspace_bytes(ab.OP_SPMM, A.n_rows, A.nnz, F), dtype=torch.uint8, device="cuda")
+
+    # cold: probes run, the decision obeys the rule on the measured times
+    s1 = h.decide(ab.OP_SPMM, A.n_rows, A.n_cols, rp, ci, va, dB, None, C, F, workspace=ws)
+    d1 = h.last_decision()
+    assert d1["cache_hit"] is False and d1["replay_miss"] is False
+    assert d1["graph_sig"] == "%016x" % oracle.graph_signature(A.rowptr, A.n_cols)
+    assert 1 <= len(d1["candidates"]) <= 3 and d1["probe_rows"] >= 512
+    t = [c["t_ms"] if c["t_ms"] is not None else float("inf") for c in d1["candidates"]]
+    assert d1["choice_index"] == oracle.decide(t, d1["t_baseline_ms"], d1["alpha"])
+    if d1["choice_index"] >= 0 and not d1.get("confirm", {}).get("demoted", False):
+        assert d1["choice"] == d1["candidates"][d1["choice_index"]]["sched"]
+        assert t[d1["choice_index"]] <= d1["alpha"] * d1["t_baseline_ms"]       # Proposition 1 on the probe times
+    else:
+        assert d1["choice"]["mapping"] == ab.MAP_PLAIN
+
+    # warm: same key -> cache hit, same schedule, nothing is timed
+    s2 = h.decide(ab.OP_SPMM, A.n_rows, A.n_cols, rp, ci, va, dB, None, C, F, workspace=ws)
+    d2 = h.last_decision()
+    assert d2["cache_hit"] is True and s2.as_dict() == s1.as_dict() and "candidates" not in d2
+    # op and F are part of the key
+    h.decide(ab.OP_SDDMM, A.n_rows, A.n_cols, rp, ci, None, dX, dB, out, F, workspace=ws)
+    assert h.last_decision()["cache_hit"] is False
+
+    # persistent cache: save, load into a fresh handle in replay-only mode -> hit without probing
+    path = str(tmp_path / "sched_cache.txt")
+    h.cache_save(path)
+    h2 = ab.Handle(0)
+    h2.set_param("replay_only", 1)
+    h2.cache_load(path)
+    s3 = h2.decide(ab.OP_SPMM, A.n_rows, A.n_cols, rp, ci, va, dB, None, C, F, workspace=ws)
+    assert h2.last_decision()["cache_hit"] is True and s3.as_dict() == s1.as_dict()
+    # replay-only miss (another F): the baseline runs and the miss is recorded
+    B2 = torch.randn(A.n_cols, 32, device="cuda")
+    C2 = torch.empty((A.n_rows, 32), dtype=torch.float32, device="cuda")
+    s4 = h2.decide(ab.OP_SPMM, A.n_rows, A.n_cols, rp, ci, va, B2, None, C2, 32, workspace=ws)
+    d4 = h2.last_decision()
+    assert d4["replay_miss"] is True and s4.mapping == ab.MAP_PLAIN and s4.hub_t == 0
+    h.close()
+    h2.close()
+
+
+@pytest.mark.parametrize("F", [16, 64, 256])
+def test_auto_path_matches_oracle_and_is_not_slower_than_fallback(torch, ab, graph, F):
+    A = graph
+    B, X = ops(torch, ab, A, F, seed=F)
+    h = ab.Handle(0)
+    rp, ci, va, dB, dX = (dev(t, torch) for t in (A.rowptr, A.colind, A.val, B, X))
+    C = torch.full((A.n_rows, F), float("nan"), dtype=torch.float32, device="cuda")
+    out = torch.full((A.nnz,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(h.workspace_bytes(ab.OP_SPMM, A.n_rows, A.nnz, F), dtype=torch.uint8, device="cuda")
+    h.spmm(A.n_rows, A.n_cols, rp, ci, va, dB, C, F, workspace=ws)            # sched = None -> selector
+    d_sp = h.last_decision()
+    h.sddmm(A.n_rows, A.n_cols, rp, ci, dX, dB, out, F, workspace=ws)
+    d_sd = h.last_decision()
+    torch.cuda.synchronize()
+    ref = oracle.spmm(A.rowptr, A.colind, A.val, B)
+    ref_abs = oracle.spmm(A.rowptr, A.colind, np.abs(A.val), np.abs(B))
+    assert rel_l1_rows(C.cpu().numpy(), ref, ref_abs).max() <= 1e-5
+    ref = oracle.sddmm(A.rowptr, A.colind, X, B)
+    ref_abs = oracle.sddmm(A.rowptr, A.colind, np.abs(X), np.abs(B))
+    assert rel_l1_segments(out.cpu().numpy(), ref, A.rowptr, ref_abs).max() <= 1e-5
+    # the skewed graph must not end on the fallback, and the choice must not lose to it on the full input
+    assert d_sp["choice"]["mapping"] != ab.MAP_PLAIN and d_sd["choice"]["mapping"] != ab.MAP_PLAIN
+    base = ab.baseline_schedule()
+    t_auto = timed(torch, lambda: h.spmm(A.n_rows, A.n_cols, rp, ci, va, dB, C, F, workspace=ws))
+    t_base = timed(torch, lambda: h.spmm(A.n_rows, A.n_cols, rp, ci, va, dB, C, F, sched=base, workspace=ws))
+    assert t_auto <= 1.05 * t_base, (t_auto, t_base)
+    t_auto = timed(torch, lambda: h.sddmm(A.n_rows, A.n_cols, rp, ci, dX, dB, out, F, workspace=ws))
+    t_base = timed(torch, lambda: h.sddmm(A.n_rows, A.n_cols, rp, ci, dX, dB, out, F, sched=base, workspace=ws))
+    assert t_auto <= 1.05 * t_base, (t_auto, t_base)
+    h.close()
+
+
+def test_guardrail_falls_back_when_alpha_is_unreachable(torch, ab, graph):
+    A, F = graph, 32
+    B, _ = ops(torch, ab, A, F)
+    h = ab.Handle(0)
+    h.set_param("alpha", 1e-6)               # no candidate can be a million times faster than the baseline
+    rp, ci, va, dB = (dev(t, torch) for t in (A.rowptr, A.colind, A.val, B))
+    C = torch.empty((A.n_rows, F), dtype=torch.float32, device="cuda")
+    ws = torch.empty(h.workspace_bytes(ab.OP_SPMM, A.n_rows, A.nnz, F), dtype=torch.uint8, device="cuda")
+    s = h.decide(ab.OP_SPMM, A.n_rows, A.n_cols, rp, ci, va, dB, None, C, F, workspace=ws)
+    d = h.last_decision()
+    assert d["choice_index"] == -1 and s.mapping == ab.MAP_PLAIN and s.as_dict() == ab.baseline_schedule().as_dict()
+    h.close()

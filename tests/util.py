@@ -11,23 +11,42 @@ def dev(a, torch, dtype=None):
     return t.cuda() if dtype is None else t.to(dtype).cuda()
 
 
-def rel_l1_rows(got, ref, eps=1e-30):
-    """Per-row L1-scaled error: ||got_i - ref_i||_1 / max(||ref_i||_1, eps); shape [rows]."""
+CANCEL_FLOOR = 0.1   # a row whose result cancels below 10 % of the magnitude of its terms is scaled by that floor
+
+
+def rel_l1_rows(got, ref, ref_abs=None, eps=1e-30):
+    """Per-row L1-scaled error: ||got_i - ref_i||_1 / max(||ref_i||_1, 0.1 * ||abs_i||_1, eps); shape [rows].
+
+    ref_abs is the same oracle result computed on the absolute values of the inputs (the sum of the
+    magnitudes of the terms of every output).  fp32 summation cannot do better than a few units of
+    2^-24 relative to that magnitude, so rows that cancel almost completely are scaled by a tenth of
+    it instead of by their (tiny) result.  Without ref_abs the plain row scaling is used."""
     got = np.asarray(got, dtype=np.float64).reshape(ref.shape[0], -1)
     ref2 = np.asarray(ref, dtype=np.float64).reshape(ref.shape[0], -1)
     num = np.abs(got - ref2).sum(axis=1)
     den = np.abs(ref2).sum(axis=1)
+    if ref_abs is not None:
+        den = np.maximum(den, CANCEL_FLOOR * np.abs(np.asarray(ref_abs, dtype=np.float64).reshape(ref.shape[0], -1)).sum(axis=1))
     return num / np.maximum(den, eps)
 
 
-def rel_l1_segments(got, ref, rowptr, eps=1e-30):
+def _segment_sums(x, rowptr):
+    rp = np.asarray(rowptr, dtype=np.int64)
+    out = np.zeros(rp.shape[0] - 1, dtype=np.float64)
+    nz = rp[1:] > rp[:-1]
+    if x.shape[0]:
+        out[nz] = np.add.reduceat(x, rp[:-1][nz])
+    return out
+
+
+def rel_l1_segments(got, ref, rowptr, ref_abs=None, eps=1e-30):
     """Same metric where "row i" is the slice rowptr[i]:rowptr[i+1] of a per-nonzero array
     (trailing dimensions, e.g. heads, are folded into the slice)."""
     got = np.asarray(got, dtype=np.float64).reshape(ref.shape[0], -1)
     ref2 = np.asarray(ref, dtype=np.float64).reshape(ref.shape[0], -1)
-    rp = np.asarray(rowptr, dtype=np.int64)
-    num = np.concatenate([[0.0], np.cumsum(np.abs(got - ref2).sum(axis=1))])
-    den = np.concatenate([[0.0], np.cumsum(np.abs(ref2).sum(axis=1))])
-    n = num[rp[1:]] - num[rp[:-1]]
-    d = den[rp[1:]] - den[rp[:-1]]
+    n = _segment_sums(np.abs(got - ref2).sum(axis=1), rowptr)
+    d = _segment_sums(np.abs(ref2).sum(axis=1), rowptr)
+    if ref_abs is not None:
+        ra = np.abs(np.asarray(ref_abs, dtype=np.float64).reshape(ref.shape[0], -1)).sum(axis=1)
+        d = np.maximum(d, CANCEL_FLOOR * _segment_sums(ra, rowptr))
     return n / np.maximum(d, eps)
