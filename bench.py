@@ -4,8 +4,8 @@
 One *step* is one pass of the whole hot path over the power-law skew stressor (N = 262144,
 mean 32 nonzeros per row, hub rows up to 65536): SpMM and SDDMM at F = 64 in fp32 with the
 schedule the selector chose (replayed from its cache; the plan/hub partition runs inside
-every call), and the multi-head CSR attention (H = 8, d = 64, bf16 operands, fp32 scores,
-SDDMM -> row-softmax -> SpMM).  All inputs are resident in HBM before the timed region.
+every call), and the multi-head CSR attention (H = 8, d = 64, bf16 operands, fp32 scores and
+accumulators; SDDMM -> row-softmax -> SpMM in the library's default single-pass form).  All inputs are resident in HBM before the timed region.
 
 Prints one JSON line: whole-step GFLOP/s (2*nnz*F per SpMM/SDDMM, 4*nnz*H*d for attention),
 the roofline of the dominant kernel measured with HIP events inside the timed region, and the
@@ -43,6 +43,9 @@ def stage_bytes(stage, N, F, H, d, light_nnz, hub_nnz, n_chunks):
         "attn_sddmm_hub": hub_nnz * (4 + 2 * HD + 4 * H),
         "attn_spmm_rows": light_nnz * (4 + 4 * H + 2 * HD) + N * 4 * HD + rp,
         "attn_spmm_hub": hub_nnz * (4 + 4 * H + 2 * HD) + 2 * n_chunks * 4 * HD,
+        # single pass: colind + one K row + one V row per nonzero; per row: Q row read, fp32 O row written
+        "attn_fused_rows": light_nnz * (4 + 4 * HD) + N * (2 * HD + 4 * HD) + rp,
+        "attn_fused_hub": hub_nnz * (4 + 4 * HD) + 2 * n_chunks * 4 * (HD + 2 * H),
         "softmax_rows": light_nnz * 8 * H + rp,
         "softmax_hub": hub_nnz * 12 * H,
         "hub_partition": 2 * rp,
@@ -151,7 +154,7 @@ def main():
         hub_nnz = int(deg[hub].sum())
         return nnz - hub_nnz, hub_nnz, int(np.ceil(deg[hub] / hub_t).sum())
 
-    hub_of = {"spmm": dec_spmm["choice"]["hub_t"], "sddmm": dec_sddmm["choice"]["hub_t"], "attn": 1024, "softmax": 1024}
+    hub_of = {"spmm": dec_spmm["choice"]["hub_t"], "sddmm": dec_sddmm["choice"]["hub_t"], "attn": 512, "softmax": 512}
     per_stage = {}
     for name, rec in stages.items():
         key = "attn" if name.startswith("attn") else name.split("_")[0]
@@ -233,9 +236,9 @@ def main():
     cpu = None
     if not args.no_cpu:
         import oracle
-        # bounded sample: the step itself on the whole graph, repeated until about 10 s of CPU work (at most 4 times)
+        # bounded sample: the step itself on the whole graph, repeated until about 12 s of CPU work (at most 16 times)
         reps, t_sp, t_at = 0, 0.0, 0.0
-        while reps < 4 and t_sp + t_at < 10.0:
+        while reps < 16 and t_sp + t_at < 12.0:
             t0 = time.perf_counter()
             oracle.spmm(A.rowptr, A.colind, A.val, B)
             oracle.sddmm(A.rowptr, A.colind, X, Y)

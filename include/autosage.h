@@ -64,7 +64,8 @@ typedef enum {
 typedef enum {
     AUTOSAGE_MAP_PLAIN = 0,      /* fallback: one wavefront per row, one lane per feature, 4-byte loads */
     AUTOSAGE_MAP_WAVE_ROW = 1,   /* one wavefront per row; lane groups split the row's nonzeros */
-    AUTOSAGE_MAP_MULTI_ROW = 2   /* several rows per wavefront: every lane group owns one row */
+    AUTOSAGE_MAP_MULTI_ROW = 2,  /* several rows per wavefront: every lane group owns one row */
+    AUTOSAGE_MAP_FUSED = 3       /* CSR attention only: one pass with a running softmax, no score array */
 } autosage_mapping_t;
 
 /* A schedule = one point of the knob space (feature tile, mapping, vector width, hub split). */
@@ -132,9 +133,14 @@ autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64_t n_rows, 
 /* CSR attention (Preliminaries: SDDMM -> row-softmax -> SpMM).  Q, K, V are [N, H, d] (in_dt, dev,
  * d minor), O is [N, H, d] fp32 dev.  S[p,h] = scale * <Q[i,h,:], K[j,h,:]>, P = row-softmax(S)
  * per (row, head), O[i,h,:] = sum_p P[p,h] V[colind[p],h,:].  Rows without nonzeros give O = 0.
- * val is ignored and may be NULL.  The [nnz, H] score array lives in the workspace.
- * sched may be NULL (library default: hub split at 1024) or give hub_t / hub_chunk / waves_per_wg /
- * unroll for all three stages; mapping, f_tile and vec_bytes are chosen from H and d. */
+ * val is ignored and may be NULL.  Requires d * element size to be a multiple of 16 bytes and 16-byte
+ * aligned Q, K, V, O (else AUTOSAGE_ERR_UNSUPPORTED).
+ * sched->mapping selects the pipeline: AUTOSAGE_MAP_FUSED = a single pass per row with a running
+ * softmax (scores never reach memory; available when the heads fit at most two register passes of a
+ * wavefront, else UNSUPPORTED); AUTOSAGE_MAP_WAVE_ROW = three stages (SDDMM -> row-softmax -> SpMM with
+ * the [nnz, H] fp32 scores in the workspace); AUTOSAGE_MAP_PLAIN (0) or sched == NULL = the library's
+ * default (single pass when available, hub split at 512 for sched == NULL).  hub_t / hub_chunk /
+ * waves_per_wg / unroll apply to every stage; f_tile and vec_bytes are chosen from H and d. */
 autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t N, int64_t nnz,
                                          const int32_t* rowptr, const int32_t* colind, const float* val,
                                          const void* Q, const void* K, const void* V, float* O,
@@ -228,7 +234,8 @@ autosage_status_t autosage_cache_insert(autosage_handle_t h, uint64_t graph_sig,
  * profile_read every kernel stage the handle launches is bracketed by a pair of HIP events on its
  * stream.  profile_read waits for the recorded stages, writes JSON {"stage":{"calls":n,"total_ms":t},...}
  * (stage names: hub_partition, spmm_rows, spmm_hub, sddmm_rows, sddmm_hub, softmax_rows, softmax_hub,
- * attn_sddmm_rows, attn_sddmm_hub, attn_spmm_rows, attn_spmm_hub) and switches profiling off. */
+ * attn_sddmm_rows, attn_sddmm_hub, attn_spmm_rows, attn_spmm_hub, attn_fused_rows, attn_fused_hub) and
+ * switches profiling off. */
 autosage_status_t autosage_profile_begin(autosage_handle_t h);
 autosage_status_t autosage_profile_read(autosage_handle_t h, char* json_buf, size_t n);
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libautosage.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_HIP, ERR_IO, ERR_REPLAY_MISS = range(7)
 F32, BF16 = 0, 1
 OP_SPMM, OP_SDDMM, OP_SOFTMAX, OP_ATTENTION = 0, 1, 2, 3
-MAP_PLAIN, MAP_WAVE_ROW, MAP_MULTI_ROW = 0, 1, 2
+MAP_PLAIN, MAP_WAVE_ROW, MAP_MULTI_ROW, MAP_FUSED = 0, 1, 2, 3
 
 
 class Schedule(ctypes.Structure):

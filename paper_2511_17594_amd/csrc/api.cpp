@@ -2,6 +2,7 @@
 // sequencing of the kernel stages.  See include/autosage.h for the contract of every entry point.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -477,7 +478,7 @@ extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, 
                                            common_alignment(C, ldc, 4), &r);
     if (s != AUTOSAGE_OK) return s;
     SpmmArgs a{};
-    a.rows = RowMap{0, 1, (int32_t)n_rows};
+    a.rows = RowMap{0, 1, (int32_t)n_rows, 0};
     a.rowptr = rowptr;
     a.colind = colind;
     a.val = val;
@@ -520,7 +521,7 @@ extern "C" autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows,
     autosage_status_t s = resolve_schedule(*sched, AUTOSAGE_OP_SDDMM, F, dt, 1, al, 16, &r);
     if (s != AUTOSAGE_OK) return s;
     SddmmArgs a{};
-    a.rows = RowMap{0, 1, (int32_t)n_rows};
+    a.rows = RowMap{0, 1, (int32_t)n_rows, 0};
     a.rowptr = rowptr;
     a.colind = colind;
     a.X = X;
@@ -570,7 +571,7 @@ extern "C" autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64
     const int chunk = hub_t > 0 ? (hub_chunk > 0 ? hub_chunk : hub_t) : 0;
     if (hub_t > 0 && chunk < kMinHubT) return AUTOSAGE_ERR_INVALID_ARG;
     SoftmaxArgs a{};
-    a.rows = RowMap{0, 1, (int32_t)n_rows};
+    a.rows = RowMap{0, 1, (int32_t)n_rows, 0};
     a.rowptr = rowptr;
     a.in = in;
     a.out = out;
@@ -581,6 +582,17 @@ extern "C" autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64
 
 // Workspace of the attention pipeline: [scores nnz*H fp32][hub metadata + partial buffer].
 static size_t attention_part_floats(int32_t H, int32_t d) { return (size_t)H * d > 2 * (size_t)H ? (size_t)H * d : 2 * (size_t)H; }
+
+// Which attention pipeline a schedule asks for: 1 = single pass, 0 = three stages, -1 = cannot run.
+static int attention_pipeline(const autosage_schedule_t* sched, int32_t H, int32_t d, int dt, AttnShape* shape)
+{
+    const bool can_fuse = attn_fused_shape(H, d, dt, shape);
+    const int mapping = sched ? sched->mapping : AUTOSAGE_MAP_PLAIN;
+    if (mapping == AUTOSAGE_MAP_FUSED) return can_fuse ? 1 : -1;
+    if (mapping == AUTOSAGE_MAP_WAVE_ROW) return 0;
+    if (mapping == AUTOSAGE_MAP_PLAIN) return can_fuse ? 1 : 0;        // library default
+    return -1;
+}
 
 extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t N, int64_t nnz,
                                                     const int32_t* rowptr, const int32_t* colind, const float* val,
@@ -610,9 +622,12 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
     autosage_schedule_t s{};
     if (sched) s = *sched;
     else {
-        s.hub_t = 1024;
-        s.hub_chunk = 1024;
+        s.hub_t = 512;
+        s.hub_chunk = 512;
     }
+    AttnShape shape{};
+    const int pipeline = attention_pipeline(sched, H, d, in_dt, &shape);
+    if (pipeline < 0) return AUTOSAGE_ERR_UNSUPPORTED;
     s.mapping = AUTOSAGE_MAP_WAVE_ROW;
     s.f_tile = 0;
     s.vec_bytes = 16;
@@ -622,6 +637,36 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
     rc = resolve_schedule(s, AUTOSAGE_OP_SPMM, (int32_t)HD, in_dt, 1, al, 16, &rp);
     if (rc != AUTOSAGE_OK) return rc;
 
+    if (pipeline == 1) {
+        // single pass with a running softmax: no score array, one hub partition, three kernels at most
+        shape.wpg = rs.wpg;
+        shape.hub_t = rs.hub_t;
+        shape.hub_chunk = rs.hub_chunk;
+        AttnArgs fa{};
+        fa.rows = RowMap{0, 1, (int32_t)N, 0};
+        fa.rowptr = rowptr;
+        fa.colind = colind;
+        fa.Q = Q;
+        fa.K = K;
+        fa.V = V;
+        fa.O = O;
+        fa.H = H;
+        fa.d = d;
+        fa.dt = in_dt;
+        fa.scale = scale;
+        HubMeta fmeta{};
+        float* fpart = nullptr;
+        if (shape.hub_t > 0) {
+            if (!carve_hub(workspace, workspace_bytes, N, nnz, shape.hub_t, shape.hub_chunk,
+                           (int64_t)attn_fused_part_floats(shape), &fmeta, &fpart, nullptr))
+                return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+            STAGE(h, "hub_partition", st, launch_hub_partition(fa.rows, rowptr, shape.hub_t, shape.hub_chunk, fmeta, st));
+        }
+        STAGE(h, "attn_fused_rows", st, launch_attn_fused_rows(fa, shape, st));
+        if (shape.hub_t > 0) STAGE(h, "attn_fused_hub", st, launch_attn_fused_hub(fa, shape, fmeta, fpart, st));
+        return AUTOSAGE_OK;
+    }
+
     const size_t score_bytes = align_up(sizeof(float) * (size_t)nnz * H, 256);
     if (!workspace || (reinterpret_cast<uint64_t>(workspace) & 255u) != 0 || workspace_bytes < score_bytes)
         return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
@@ -629,7 +674,7 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
     char* hub_ws = static_cast<char*>(workspace) + score_bytes;
     const size_t hub_ws_bytes = workspace_bytes - score_bytes;
 
-    const RowMap rows{0, 1, (int32_t)N};
+    const RowMap rows{0, 1, (int32_t)N, 0};
     HubMeta meta{};
     float* part = nullptr;
     if (rs.hub_t > 0) {
@@ -695,17 +740,28 @@ extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autos
         chunk = sched->hub_t > 0 ? (sched->hub_chunk > 0 ? sched->hub_chunk : sched->hub_t) : 0;
         if (hub_t < 0 || (hub_t > 0 && (hub_t < kMinHubT || chunk < kMinHubT))) return AUTOSAGE_ERR_INVALID_ARG;
     } else if (op == AUTOSAGE_OP_ATTENTION) {
-        hub_t = chunk = 1024;
+        hub_t = chunk = 512;
     }
     size_t b = 0;
     switch (op) {
         case AUTOSAGE_OP_SPMM: b = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, F); break;
         case AUTOSAGE_OP_SDDMM: b = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, 0); break;
         case AUTOSAGE_OP_SOFTMAX: b = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, 2 * (int64_t)H); break;
-        case AUTOSAGE_OP_ATTENTION:
-            b = align_up(sizeof(float) * (size_t)nnz * H, 256) +
-                hub_workspace_bytes(n_rows, nnz, hub_t, chunk, (int64_t)attention_part_floats(H, F));
+        case AUTOSAGE_OP_ATTENTION: {
+            // dtype is not an argument here: take the larger per-chunk state of the two element types
+            AttnShape sh{};
+            size_t fused_floats = 0;
+            for (int dt = 0; dt <= 1; ++dt)
+                if (attn_fused_shape(H, F, dt, &sh)) fused_floats = std::max(fused_floats, attn_fused_part_floats(sh));
+            const size_t three = align_up(sizeof(float) * (size_t)nnz * H, 256) +
+                                 hub_workspace_bytes(n_rows, nnz, hub_t, chunk, (int64_t)attention_part_floats(H, F));
+            const size_t fused = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, (int64_t)fused_floats);
+            const int mapping = sched ? sched->mapping : AUTOSAGE_MAP_PLAIN;
+            if (mapping == AUTOSAGE_MAP_FUSED) b = fused;
+            else if (mapping == AUTOSAGE_MAP_WAVE_ROW) b = three;
+            else b = std::max(three, fused);
             break;
+        }
         default: return AUTOSAGE_ERR_INVALID_ARG;
     }
     *bytes = b < 256 ? 256 : b;
@@ -737,7 +793,7 @@ extern "C" autosage_status_t autosage_hub_partition(autosage_handle_t h, int64_t
     meta.light_rows = light_rows;
     meta.cap_hub = (int32_t)n_rows;
     meta.cap_chunks = 0;
-    HIP_TRY(launch_hub_partition(RowMap{0, 1, (int32_t)n_rows}, rowptr, hub_t, hub_chunk, meta, st));
+    HIP_TRY(launch_hub_partition(RowMap{0, 1, (int32_t)n_rows, 0}, rowptr, hub_t, hub_chunk, meta, st));
     HubCounts c{};
     HIP_TRY(hipMemcpyAsync(&c, meta.counts, sizeof c, hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));

@@ -45,8 +45,8 @@ struct Params {
     double probe_frac = 0.02;
     int probe_iters = 5;
     double probe_cap_ms = 1.0;
-    int probe_topk = 3;
-    int probe_min_rows = 512;
+    int probe_topk = 4;
+    int probe_min_rows = 16384;
     int replay_only = 0;
     int confirm_full = 1;
     int memoize_signature = 1;

@@ -1,7 +1,7 @@
 // Host-side launcher interface between the C ABI layer and the kernel translation units.
 // Everything here is plain data + free functions; no device code.
 #pragma once
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -10,13 +10,20 @@ namespace autosage {
 enum Mapping { MAP_PLAIN = 0, MAP_WAVE_ROW = 1, MAP_MULTI_ROW = 2 };
 enum DType { DT_F32 = 0, DT_BF16 = 1 };
 
-// The rows a launch covers: row(idx) = first + idx * stride for idx in [0, count).
-// The full matrix is {0, 1, n_rows}; a probe uses a strided sample of the same arrays.
+// The rows a launch covers, in blocks of 2^block_shift consecutive rows:
+//   row(idx) = first + (idx >> block_shift) * stride + (idx & (2^block_shift - 1)),  idx in [0, count).
+// The full matrix is {0, 1, n_rows, 0}; a probe uses strided blocks of rows of the same arrays.
 struct RowMap {
     int32_t first;
-    int32_t stride;
+    int32_t stride;        // distance between the first rows of consecutive blocks
     int32_t count;
+    int32_t block_shift;
 };
+
+__host__ __device__ inline int32_t row_of(const RowMap& m, int32_t idx)
+{
+    return m.first + (idx >> m.block_shift) * m.stride + (idx & ((1 << m.block_shift) - 1));
+}
 
 // A schedule with every "auto" field resolved against F, dtype and alignment.
 struct Resolved {
@@ -89,6 +96,39 @@ struct SoftmaxArgs {
     float* out;            // [nnz, H]
     int32_t H;
 };
+
+struct AttnArgs {
+    RowMap rows;
+    const int32_t* rowptr;
+    const int32_t* colind;
+    const void* Q;         // [n_rows, H, d]
+    const void* K;         // [n_cols, H, d]
+    const void* V;         // [n_cols, H, d]
+    float* O;              // [n_rows, H, d]
+    int32_t H;
+    int32_t d;
+    int32_t dt;
+    float scale;
+};
+
+// Lane shape of the single-pass attention kernels: LH lanes per head, HW heads side by side,
+// KH head passes kept in registers.
+struct AttnShape {
+    int32_t vec;
+    int32_t LH;
+    int32_t HW;
+    int32_t KH;
+    int32_t wpg;
+    int32_t hub_t;
+    int32_t hub_chunk;
+};
+
+// True (and fills vec/LH/HW/KH) when the single-pass kernels cover this head count and width.
+bool attn_fused_shape(int32_t H, int32_t d, int dt, AttnShape* s);
+// Floats of partial state per hub chunk.
+size_t attn_fused_part_floats(const AttnShape& s);
+hipError_t launch_attn_fused_rows(const AttnArgs& a, const AttnShape& s, hipStream_t stream);
+hipError_t launch_attn_fused_hub(const AttnArgs& a, const AttnShape& s, const HubMeta& meta, float* part, hipStream_t stream);
 
 // Heavy/light partition of the rows of `rows` (index metadata, integer only).
 hipError_t launch_hub_partition(const RowMap& rows, const int32_t* rowptr, int32_t hub_t, int32_t hub_chunk,

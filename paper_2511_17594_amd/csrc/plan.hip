@@ -29,7 +29,7 @@ struct PartDev {
 
 __device__ __forceinline__ int row_degree(const PartDev& a, int idx)
 {
-    const int row = a.rows.first + idx * a.rows.stride;
+    const int row = row_of(a.rows, idx);
     return a.rowptr[row + 1] - a.rowptr[row];
 }
 

@@ -490,16 +490,41 @@ extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t 
     else al = std::min(al, common_alignment(out, ld_out, 4));
     std::vector<autosage_schedule_t> cands;
     std::vector<double> est;
-    shortlist(h, op, n_rows, n_cols, nnz, hist, max_deg, F, dt, al, &cands, &est);
-    const int topk = std::max(0, std::min<int>(h->params.probe_topk, (int)cands.size()));
+    {
+        // the probes get the best-ranked candidates that differ in more than the unroll depth
+        std::vector<autosage_schedule_t> all;
+        std::vector<double> all_est;
+        shortlist(h, op, n_rows, n_cols, nnz, hist, max_deg, F, dt, al, &all, &all_est);
+        for (size_t i = 0; i < all.size() && (int)cands.size() < h->params.probe_topk; ++i) {
+            bool fresh = true;
+            for (const autosage_schedule_t& c : cands)
+                if (c.mapping == all[i].mapping && c.hub_t == all[i].hub_t && c.xcd_remap == all[i].xcd_remap &&
+                    c.vec_bytes == all[i].vec_bytes)
+                    fresh = false;
+            if (fresh) {
+                cands.push_back(all[i]);
+                est.push_back(all_est[i]);
+            }
+        }
+    }
+    const int topk = (int)cands.size();
 
-    // 4. probes on a strided row sample (all candidates see the identical sample)
-    int64_t stride = (int64_t)std::floor(1.0 / h->params.probe_frac);
-    if (stride < 1) stride = 1;
+    // 4. probes on a sample of row blocks, run in place (all candidates see the identical sample).
+    // Blocks of 256 consecutive rows keep the locality between neighbouring rows that a single-row
+    // stride would destroy; the blocks are spread evenly over the matrix.
     const int64_t min_rows = std::max(1, h->params.probe_min_rows);
-    if (n_rows / stride < min_rows) stride = std::max<int64_t>(1, n_rows / min_rows);
-    RowMap sample{(int32_t)(stride / 2), (int32_t)stride, 0};
-    sample.count = n_rows > sample.first ? (int32_t)((n_rows - sample.first + stride - 1) / stride) : 0;
+    int64_t target = std::max<int64_t>(min_rows, (int64_t)std::ceil(h->params.probe_frac * (double)n_rows));
+    RowMap sample{0, 1, (int32_t)n_rows, 0};
+    int64_t stride = 1;
+    if (target < n_rows) {
+        const int shift = 8;
+        const int64_t block = int64_t(1) << shift;
+        const int64_t nb = std::max<int64_t>(1, target / block);
+        if (nb * block < n_rows) {
+            stride = n_rows / nb;                 // >= block
+            sample = RowMap{(int32_t)((stride - block) / 2), (int32_t)stride, (int32_t)(nb * block), shift};
+        }
+    }
     OpInput in{(int)op, n_rows, n_cols, nnz, rowptr, colind, val, dense0, ld0, dense1, ld1, out, ld_out, F, (int)dt};
 
     const double tb = time_schedule(h, in, sample, base, workspace, workspace_bytes, st, h->params.probe_iters,
@@ -523,7 +548,7 @@ extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t 
 
     // 6. the guardrail speaks about the sample; confirm once on the whole input
     if (choice >= 0 && h->params.confirm_full) {
-        const RowMap full{0, 1, (int32_t)n_rows};
+        const RowMap full{0, 1, (int32_t)n_rows, 0};
         const double cap = std::numeric_limits<double>::infinity();
         const double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, cap);
         const double tf_b = time_schedule(h, in, full, base, workspace, workspace_bytes, st, 2, cap);

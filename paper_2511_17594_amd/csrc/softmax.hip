@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(1024) softmax_rows_kernel(SoftmaxDev a)
     const int lane = threadIdx.x & (kWave - 1);
     const int idx = wave_uniform(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
     if (idx >= a.rows.count) return;
-    const int row = a.rows.first + idx * a.rows.stride;
+    const int row = row_of(a.rows, idx);
     const int p0 = wave_uniform(a.rowptr[row]);
     const int p1 = wave_uniform(a.rowptr[row + 1]);
     const int deg = p1 - p0;
@@ -159,7 +159,7 @@ __global__ void __launch_bounds__(1024) softmax_hub_partial_kernel(SoftmaxDev a)
     const int wave = threadIdx.x >> 6;
     const int wpg = blockDim.x >> 6;
     const int k_hub = softmax_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
-    const int row = a.rows.first + a.hub_rows[k_hub] * a.rows.stride;
+    const int row = row_of(a.rows, a.hub_rows[k_hub]);
     const int t = chunk - a.chunk_ptr[k_hub];
     const int q0 = a.rowptr[row] + t * a.hub_chunk;
     const int q1 = min(q0 + a.hub_chunk, a.rowptr[row + 1]);
@@ -202,7 +202,7 @@ __global__ void __launch_bounds__(1024) softmax_hub_normalise_kernel(SoftmaxDev 
     const int wave = threadIdx.x >> 6;
     const int wpg = blockDim.x >> 6;
     const int k_hub = softmax_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
-    const int row = a.rows.first + a.hub_rows[k_hub] * a.rows.stride;
+    const int row = row_of(a.rows, a.hub_rows[k_hub]);
     const int c0 = a.chunk_ptr[k_hub];
     const int c1 = a.chunk_ptr[k_hub + 1];
     const int t = chunk - c0;

@@ -13,7 +13,7 @@ __global__ void __launch_bounds__(256) spmm_hub_combine_kernel(SpmmDev a)
 {
     const int k_hub = blockIdx.x;
     if (k_hub >= a.counts->n_hub) return;
-    const int row = a.rows.first + a.hub_rows[k_hub] * a.rows.stride;
+    const int row = row_of(a.rows, a.hub_rows[k_hub]);
     const int c0 = a.chunk_ptr[k_hub];
     const int c1 = a.chunk_ptr[k_hub + 1];
     for (int f = threadIdx.x; f < a.F; f += blockDim.x) {

@@ -134,19 +134,22 @@ def test_config5_attention_full_size(torch, ab, handle, config2):
     As = W.row_slice(A, rows)
     for qk_std in (None, 1.0):                                           # the config's flat softmax and a peaked one
         Q, K, V = W.config5_attention(A.n_rows, H, d, seed=0, qk_std=qk_std)
-        O = torch.full((A.n_rows, H, d), float("nan"), dtype=torch.float32, device="cuda")
-        ws = torch.empty(handle.workspace_bytes(ab.OP_ATTENTION, A.n_rows, A.nnz, d, H), dtype=torch.uint8, device="cuda")
-        handle.csr_attention(A.n_rows, dev(A.rowptr, torch), dev(A.colind, torch), dev(Q, torch), dev(K, torch),
-                             dev(V, torch), O, H, d, scale, workspace=ws)
-        torch.cuda.synchronize()
-        assert bool(torch.isfinite(O).all())
-        got = O[torch.from_numpy(rows).cuda()].cpu().numpy()
+        d_in = [dev(t, torch) for t in (A.rowptr, A.colind, Q, K, V)]
         ref = oracle.csr_attention(As.rowptr, As.colind, np.ascontiguousarray(Q[rows]), K, V, scale)
-        err = rel_l1_rows(got.reshape(-1, d), ref.reshape(-1, d))
-        assert err.max() <= 2e-2, (qk_std, float(err.max()))
-        # every output row is a convex combination of V rows: bounded by the extreme V values of its head
         vmax = float(np.abs(W.bf16_bits_to_float(V)).max())
-        assert float(O.abs().max()) <= vmax * (1 + 1e-5)
+        for sched in (None, ab.Schedule(mapping=ab.MAP_WAVE_ROW, hub_t=1024, hub_chunk=1024)):   # default, three stages
+            O = torch.full((A.n_rows, H, d), float("nan"), dtype=torch.float32, device="cuda")
+            ws = torch.empty(handle.workspace_bytes(ab.OP_ATTENTION, A.n_rows, A.nnz, d, H, sched), dtype=torch.uint8,
+                             device="cuda")
+            handle.csr_attention(A.n_rows, *d_in, O, H, d, scale, sched=sched, workspace=ws)
+            torch.cuda.synchronize()
+            assert bool(torch.isfinite(O).all())
+            got = O[torch.from_numpy(rows).cuda()].cpu().numpy()
+            err = rel_l1_rows(got.reshape(-1, d), ref.reshape(-1, d))
+            assert err.max() <= 2e-2, (qk_std, float(err.max()))
+            # every output row is a convex combination of V rows: bounded by the extreme V value
+            assert float(O.abs().max()) <= vmax * (1 + 1e-5)
+            del O, ws
 
 
 def test_config3_community_full_size(torch, ab, handle):

@@ -205,20 +205,45 @@ def test_csr_attention(torch, handle, ab, skew_graph, H, d, dtype, qk_std, hub_t
         Q, K, V, tol, dt = Qb, Kb, Vb, TOL_BF16, ab.BF16
     scale = float(d) ** -0.5
     ref = oracle.csr_attention(A.rowptr, A.colind, Q, K, V, scale)
-    s = sched_of(ab, hub_t=hub_t, hub_chunk=hub_t)
-    O = torch.full((A.n_rows, H, d), float("nan"), dtype=torch.float32, device="cuda")
-    ws = torch.empty(handle.workspace_bytes(ab.OP_ATTENTION, A.n_rows, A.nnz, d, H, s), dtype=torch.uint8, device="cuda")
-    handle.csr_attention(A.n_rows, dev(A.rowptr, torch), dev(A.colind, torch), dev(Q, torch), dev(K, torch),
-                         dev(V, torch), O, H, d, scale, in_dt=dt, sched=s, workspace=ws, nnz=A.nnz)
+    d_in = [dev(t, torch) for t in (A.rowptr, A.colind, Q, K, V)]
+    for mapping in (ab.MAP_WAVE_ROW, ab.MAP_FUSED):                # three stages, and the single pass
+        s = sched_of(ab, mapping=mapping, hub_t=hub_t, hub_chunk=hub_t)
+        O = torch.full((A.n_rows, H, d), float("nan"), dtype=torch.float32, device="cuda")
+        ws = torch.empty(handle.workspace_bytes(ab.OP_ATTENTION, A.n_rows, A.nnz, d, H, s), dtype=torch.uint8, device="cuda")
+        handle.csr_attention(A.n_rows, d_in[0], d_in[1], d_in[2], d_in[3], d_in[4], O, H, d, scale, in_dt=dt, sched=s,
+                             workspace=ws, nnz=A.nnz)
+        torch.cuda.synchronize()
+        got = O.cpu().numpy()
+        assert np.isfinite(got).all(), mapping
+        err = rel_l1_rows(got.reshape(A.n_rows * H, d), ref.reshape(A.n_rows * H, d))
+        assert err.max() <= tol, (mapping, H, d, dtype, float(err.max()), int(err.argmax()))
+        assert np.all(got[A.degrees == 0] == 0.0), mapping
+        # the bf16 path is in fact far inside its tolerance: inputs are exact, only fp32 rounding differs
+        if dtype == "bf16":
+            assert err.max() <= 1e-4, mapping
+
+
+def test_csr_attention_unsupported_shapes(torch, handle, ab, skew_graph):
+    A = skew_graph
+    rp, ci = dev(A.rowptr, torch), dev(A.colind, torch)
+    ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+
+    def call(H, d, mapping):
+        Q = torch.zeros((A.n_rows, H, d), dtype=torch.bfloat16, device="cuda")
+        O = torch.zeros((A.n_rows, H, d), dtype=torch.float32, device="cuda")
+        handle.csr_attention(A.n_rows, rp, ci, Q, Q, Q, O, H, d, 1.0, sched=sched_of(ab, mapping=mapping), workspace=ws,
+                             nnz=A.nnz)
+
+    with pytest.raises(ab.AutosageError) as ei:
+        call(4, 12, ab.MAP_WAVE_ROW)              # 24-byte head rows cannot take 16-byte lane loads
+    assert ei.value.status == ab.ERR_UNSUPPORTED
+    with pytest.raises(ab.AutosageError) as ei:
+        call(32, 64, ab.MAP_FUSED)                # 32 heads x 8 lanes = four register passes: single pass not built
+    assert ei.value.status == ab.ERR_UNSUPPORTED
+    with pytest.raises(ab.AutosageError) as ei:
+        call(8, 64, ab.MAP_MULTI_ROW)             # not an attention pipeline
+    assert ei.value.status == ab.ERR_UNSUPPORTED
     torch.cuda.synchronize()
-    got = O.cpu().numpy()
-    assert np.isfinite(got).all()
-    err = rel_l1_rows(got.reshape(A.n_rows * H, d), ref.reshape(A.n_rows * H, d))
-    assert err.max() <= tol, (H, d, dtype, float(err.max()), int(err.argmax()))
-    assert np.all(got[A.degrees == 0] == 0.0)
-    # the bf16 path is in fact far inside its tolerance: inputs are exact, only fp32 rounding differs
-    if dtype == "bf16":
-        assert err.max() <= 1e-4
 
 
 @pytest.mark.parametrize("hub_t,chunk", [(64, 64), (256, 100), (1, 7), (5000, 64)])

@@ -61,7 +61,9 @@ def test_decide_probe_guardrail_cache_replay(torch, ab, graph, tmp_path):
     d1 = h.last_decision()
     assert d1["cache_hit"] is False and d1["replay_miss"] is False
     assert d1["graph_sig"] == "%016x" % oracle.graph_signature(A.rowptr, A.n_cols)
-    assert 1 <= len(d1["candidates"]) <= 3 and d1["probe_rows"] >= 512
+    assert 1 <= len(d1["candidates"]) <= 4 and d1["probe_rows"] >= 512
+    keys = [(c["sched"]["mapping"], c["sched"]["hub_t"], c["sched"]["xcd_remap"], c["sched"]["vec_bytes"]) for c in d1["candidates"]]
+    assert len(set(keys)) == len(keys)                       # the probed candidates differ in more than the unroll depth
     t = [c["t_ms"] if c["t_ms"] is not None else float("inf") for c in d1["candidates"]]
     assert d1["choice_index"] == oracle.decide(t, d1["t_baseline_ms"], d1["alpha"])
     if d1["choice_index"] >= 0 and not d1.get("confirm", {}).get("demoted", False):

@@ -63,7 +63,7 @@ def test_decision_rule_matches_oracle_and_never_regresses(ab):
 def test_params_and_baseline(ab, host):
     assert host.get_param("alpha") == pytest.approx(0.95)
     assert host.get_param("probe_frac") == pytest.approx(0.02)
-    assert host.get_param("probe_min_rows") == 512
+    assert host.get_param("probe_min_rows") == 16384
     host.set_param("alpha", 0.98)
     assert host.get_param("alpha") == pytest.approx(0.98)
     for bad in (("alpha", 0.0), ("probe_frac", 1.5), ("probe_iters", 0), ("no_such_param", 1.0)):
