@@ -375,27 +375,32 @@ autosage_status_t run_once(autosage_ctx* h, const OpInput& in, const RowMap& row
     return exec_sddmm(h, a, r, in.nnz, ws, ws_bytes, st);
 }
 
-// Median of up to `iters` timed runs (one untimed warm-up first); stops early once the timed
-// runs add up to cap_ms.  Returns +inf when the schedule cannot run on this input.
+// Median of up to `iters` timed runs after one warm-up run; stops early once the timed runs add up
+// to cap_ms.  The warm-up is timed as well: when it alone takes four caps or more (a slow schedule
+// on this input) it is returned as the measurement, since cold-start effects are negligible at that
+// length and repeating it would only burn time.  Returns +inf when the schedule cannot run.
 double time_schedule(autosage_ctx* h, const OpInput& in, const RowMap& rows, const autosage_schedule_t& s, void* ws,
                      size_t ws_bytes, hipStream_t st, int iters, double cap_ms)
 {
     const double inf = std::numeric_limits<double>::infinity();
-    if (run_once(h, in, rows, s, ws, ws_bytes, st) != AUTOSAGE_OK) return inf;
-    if (hipStreamSynchronize(st) != hipSuccess) return inf;
     std::vector<double> t;
     double total = 0.0;
-    for (int i = 0; i < iters; ++i) {
+    for (int i = -1; i < iters; ++i) {
         if (hipEventRecord(h->ev0, st) != hipSuccess) return inf;
         if (run_once(h, in, rows, s, ws, ws_bytes, st) != AUTOSAGE_OK) return inf;
         if (hipEventRecord(h->ev1, st) != hipSuccess) return inf;
         if (hipEventSynchronize(h->ev1) != hipSuccess) return inf;
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, h->ev0, h->ev1) != hipSuccess) return inf;
+        if (i < 0) {                                  // warm-up
+            if (ms >= 4.0 * cap_ms) return ms;
+            continue;
+        }
         t.push_back(ms);
         total += ms;
         if (total >= cap_ms) break;
     }
+    if (t.empty()) return inf;
     std::sort(t.begin(), t.end());
     return t[t.size() / 2];
 }
@@ -551,7 +556,8 @@ extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t 
         const RowMap full{0, 1, (int32_t)n_rows, 0};
         const double cap = std::numeric_limits<double>::infinity();
         const double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, cap);
-        const double tf_b = time_schedule(h, in, full, base, workspace, workspace_bytes, st, 2, cap);
+        // a baseline run that already takes more than twice the choice settles the question in one run
+        const double tf_b = time_schedule(h, in, full, base, workspace, workspace_bytes, st, 2, 0.5 * tf_c);
         const bool demote = !(tf_c <= tf_b);
         js << ",\"confirm\":{\"t_choice_ms\":" << num(tf_c) << ",\"t_baseline_ms\":" << num(tf_b) << ",\"demoted\":"
            << (demote ? "true" : "false") << "}";

@@ -1,0 +1,131 @@
+"""Feature-width sweep of SpMM / SDDMM on one of the synthetic workloads, printed as a Markdown table.
+
+    python -m paper_2511_17594_amd.sweep --workload config2 [--widths 8,16,32,64,128,256] [--vendor]
+
+For every width: the selector's choice (cold call, then steady state from its cache), time (median of
+`--iters` HIP-event timings), GFLOP/s = 2*nnz*F/t, algorithmic GB/s (every gathered dense row counted
+once per nonzero) and its fraction of the 8 TB/s HBM peak, and the guardrail's fallback kernel on the
+same input.  `--vendor` adds the vendor SpMM reached through torch.sparse.mm.  Workloads: config1..4
+(the benchmark configurations), er (Erdos-Renyi N = 200000, p = 2e-5, the shape of the paper's
+extreme-sparsity stressor) and hubsplit_5k / hubsplit_12k (N = 20000, a few rows of degree 5000 /
+12000, the rest 64 / 32: the shape of the paper's split-versus-baseline table; the number of hub rows
+is not given there, 32 is used).
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+DEFAULT_WIDTHS = {
+    "config1": [32], "config2": [8, 16, 32, 64, 128, 256], "config3": [32, 64, 128, 256, 602],
+    "config4": [16, 32, 100, 128], "er": [64, 128, 256], "hubsplit_5k": [128], "hubsplit_12k": [128],
+}
+
+
+def make_workload(name):
+    from . import workloads as W
+    if name == "config1":
+        return W.config1_tiny()[0]
+    if name == "config2":
+        return W.config2_powerlaw()
+    if name == "config3":
+        return W.config3_community()
+    if name == "config4":
+        return W.config4_large()
+    if name == "er":
+        return W.er_graph(200000, 2e-5, seed=0, config_id=7)
+    if name == "hubsplit_5k":
+        return W.hub_split_graph(20000, 32, 5000, 64)
+    if name == "hubsplit_12k":
+        return W.hub_split_graph(20000, 32, 12000, 32)
+    raise SystemExit("unknown workload %r" % name)
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--workload", default="config2", choices=sorted(DEFAULT_WIDTHS))
+    ap.add_argument("--widths", default=None)
+    ap.add_argument("--iters", type=int, default=10)
+    ap.add_argument("--vendor", action="store_true")
+    ap.add_argument("--no-sddmm", action="store_true")
+    args = ap.parse_args(argv)
+
+    import torch
+    from . import binding as ab
+
+    widths = [int(x) for x in args.widths.split(",")] if args.widths else DEFAULT_WIDTHS[args.workload]
+    t0 = time.time()
+    A = make_workload(args.workload)
+    N, M, nnz = A.n_rows, A.n_cols, A.nnz
+    deg = A.degrees
+    print("workload %s: rows %d, nnz %d, degree mean %.1f / median %d / max %d (generated in %.1f s)"
+          % (args.workload, N, nnz, deg.mean(), int(np.median(deg)), int(deg.max()), time.time() - t0), file=sys.stderr)
+    rp = torch.from_numpy(A.rowptr).cuda()
+    ci = torch.from_numpy(A.colind).cuda()
+    va = torch.from_numpy(A.val).cuda()
+    h = ab.Handle(0)
+    stream = torch.cuda.current_stream()
+    base = ab.baseline_schedule()
+
+    def timed(fn, iters):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(iters):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return float(np.median(ts))
+
+    def short(c):
+        m = {0: "plain", 1: "wave-row", 2: "multi-row"}[c["mapping"]]
+        return "%s v%d u%d hub %d%s" % (m, c["vec_bytes"], c["unroll"], c["hub_t"], " xcd" if c["xcd_remap"] else "")
+
+    print("| op | F | ms | GFLOP/s | GB/s | of 8 TB/s | fallback ms | speed-up | cold call ms | selector's choice |")
+    print("|---|---|---|---|---|---|---|---|---|---|")
+    for F in widths:
+        g = torch.Generator(device="cuda").manual_seed(F)
+        B = torch.randn((M, F), device="cuda", generator=g)
+        X = torch.randn((N, F), device="cuda", generator=g)
+        C = torch.empty((N, F), device="cuda")
+        out = torch.empty(max(nnz, 1), device="cuda")
+        ws = torch.empty(h.workspace_bytes(ab.OP_SPMM, N, nnz, F), dtype=torch.uint8, device="cuda")
+        bg = 4 * (N + 1) + 8 * nnz + nnz * F * 4 + N * F * 4
+        ops = [("SpMM", lambda s: h.spmm(N, M, rp, ci, va, B, C, F, sched=s, workspace=ws, stream=stream))]
+        if not args.no_sddmm:
+            ops.append(("SDDMM", lambda s: h.sddmm(N, M, rp, ci, X, B, out, F, sched=s, workspace=ws, stream=stream, nnz=nnz)))
+        for name, fn in ops:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn(None)
+            torch.cuda.synchronize()
+            cold = (time.perf_counter() - t0) * 1e3
+            choice = h.last_decision().get("choice")
+            t = timed(lambda: fn(None), args.iters)
+            tb = timed(lambda: fn(base), 3)
+            print("| %s | %d | %.3f | %.0f | %.0f | %.0f %% | %.3f | %.2fx | %.1f | %s |"
+                  % (name, F, t, 2.0 * nnz * F / t / 1e6, bg / t / 1e6, 100 * bg / t / 1e6 / HBM_PEAK_GBS, tb, tb / t, cold,
+                     short(choice)), flush=True)
+        if args.vendor:
+            try:
+                Asp = torch.sparse_csr_tensor(rp.to(torch.int64), ci.to(torch.int64), va, size=(N, M))
+                tv = timed(lambda: torch.sparse.mm(Asp, B), 3)
+                print("| vendor SpMM (torch.sparse.mm) | %d | %.3f | %.0f | %.0f | %.0f %% | | | | |"
+                      % (F, tv, 2.0 * nnz * F / tv / 1e6, bg / tv / 1e6, 100 * bg / tv / 1e6 / HBM_PEAK_GBS), flush=True)
+                del Asp
+            except Exception as e:                      # pragma: no cover
+                print("vendor SpMM unavailable: %r" % (e,), file=sys.stderr)
+        del B, X, C, out, ws
+    h.close()
+
+
+if __name__ == "__main__":
+    main()
