@@ -5,7 +5,7 @@ One *step* is one pass of the whole hot path over the power-law skew stressor (N
 mean 32 nonzeros per row, hub rows up to 65536): SpMM and SDDMM at F = 64 in fp32 with the
 schedule the selector chose (replayed from its cache; the plan/hub partition runs inside
 every call), and the multi-head CSR attention (H = 8, d = 64, bf16 operands, fp32 scores and
-accumulators; SDDMM -> row-softmax -> SpMM in the library's default single-pass form).  All inputs are resident in HBM before the timed region.
+accumulators; SDDMM -> row-softmax -> SpMM in the pipeline form and hub threshold the selector chose).  All inputs are resident in HBM before the timed region.
 
 Prints one JSON line: whole-step GFLOP/s (2*nnz*F per SpMM/SDDMM, 4*nnz*H*d for attention),
 the roofline of the dominant kernel measured with HIP events inside the timed region, and the
@@ -127,6 +127,12 @@ def main():
     torch.cuda.synchronize()
     cold_sddmm_ms = (time.perf_counter() - t0) * 1e3
     dec_sddmm = h.last_decision()
+    t0 = time.perf_counter()
+    h.csr_attention(N, rp, ci, dQ, dK, dV, O, H, d, scale, workspace=ws, stream=stream)
+    torch.cuda.synchronize()
+    cold_attn_ms = (time.perf_counter() - t0) * 1e3
+    dec_attn = h.last_decision()
+    log("selector attn : %s (cold call %.2f ms)" % (dec_attn.get("choice"), cold_attn_ms))
     log("selector spmm : %s (cold call %.2f ms)" % (dec_spmm.get("choice"), cold_spmm_ms))
     log("selector sddmm: %s (cold call %.2f ms)" % (dec_sddmm.get("choice"), cold_sddmm_ms))
 
@@ -154,7 +160,7 @@ def main():
         hub_nnz = int(deg[hub].sum())
         return nnz - hub_nnz, hub_nnz, int(np.ceil(deg[hub] / hub_t).sum())
 
-    hub_of = {"spmm": dec_spmm["choice"]["hub_t"], "sddmm": dec_sddmm["choice"]["hub_t"], "attn": 512, "softmax": 512}
+    hub_of = {"spmm": dec_spmm["choice"]["hub_t"], "sddmm": dec_sddmm["choice"]["hub_t"], "attn": dec_attn["choice"]["hub_t"], "softmax": dec_attn["choice"]["hub_t"]}
     per_stage = {}
     for name, rec in stages.items():
         key = "attn" if name.startswith("attn") else name.split("_")[0]
@@ -264,8 +270,8 @@ def main():
                    "N": N, "nnz": nnz, "F": F, "H": H, "d": d},
         "roofline": roofline,
         "cpu_baseline": cpu,
-        "selector": {"spmm": dec_spmm.get("choice"), "sddmm": dec_sddmm.get("choice"),
-                     "cold_call_ms": {"spmm": cold_spmm_ms, "sddmm": cold_sddmm_ms}},
+        "selector": {"spmm": dec_spmm.get("choice"), "sddmm": dec_sddmm.get("choice"), "attention": dec_attn.get("choice"),
+                     "cold_call_ms": {"spmm": cold_spmm_ms, "sddmm": cold_sddmm_ms, "attention": cold_attn_ms}},
         "stages": {k: {"avg_ms": v["avg_ms"], "gbs": v["gbs"]} for k, v in per_stage.items()},
         "detail": detail,
     }

@@ -137,10 +137,11 @@ autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64_t n_rows, 
  * aligned Q, K, V, O (else AUTOSAGE_ERR_UNSUPPORTED).
  * sched->mapping selects the pipeline: AUTOSAGE_MAP_FUSED = a single pass per row with a running
  * softmax (scores never reach memory; available when the heads fit at most two register passes of a
- * wavefront, else UNSUPPORTED); AUTOSAGE_MAP_WAVE_ROW = three stages (SDDMM -> row-softmax -> SpMM with
- * the [nnz, H] fp32 scores in the workspace); AUTOSAGE_MAP_PLAIN (0) or sched == NULL = the library's
- * default (single pass when available, hub split at 512 for sched == NULL).  hub_t / hub_chunk /
- * waves_per_wg / unroll apply to every stage; f_tile and vec_bytes are chosen from H and d. */
+ * wavefront, else UNSUPPORTED); AUTOSAGE_MAP_WAVE_ROW or AUTOSAGE_MAP_PLAIN = three stages (SDDMM ->
+ * row-softmax -> SpMM with the [nnz, H] fp32 scores in the workspace); the guardrail baseline is the
+ * three-stage pipeline without hub split (autosage_baseline_schedule).  hub_t / hub_chunk / waves_per_wg /
+ * unroll apply to every stage; f_tile and vec_bytes are chosen from H and d.
+ * sched == NULL: the selector chooses pipeline and hub threshold (autosage_decide_attention). */
 autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t N, int64_t nnz,
                                          const int32_t* rowptr, const int32_t* colind, const float* val,
                                          const void* Q, const void* K, const void* V, float* O,
@@ -215,6 +216,15 @@ autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t op, int64_t
                                   void* workspace, size_t workspace_bytes, void* stream,
                                   autosage_schedule_t* chosen);
 
+/* The same decision for CSR attention (key: device signature, graph signature, d, H, dtype).
+ * Candidates: single pass and three stages over a few hub thresholds; baseline: three stages without
+ * hub split.  O is used as the probe target and is left undefined. */
+autosage_status_t autosage_decide_attention(autosage_handle_t h, int64_t N, int64_t nnz, const int32_t* rowptr,
+                                            const int32_t* colind, const void* Q, const void* K, const void* V,
+                                            float* O, int32_t H, int32_t d, float scale, autosage_dtype_t dt,
+                                            void* workspace, size_t workspace_bytes, void* stream,
+                                            autosage_schedule_t* chosen);
+
 /* JSON text of the most recent decision of this handle (key, candidates, probe times, choice,
  * alpha, cache hit / replay miss flags).  Truncated to n-1 characters. */
 autosage_status_t autosage_last_decision(autosage_handle_t h, char* json_buf, size_t n);
@@ -224,11 +234,13 @@ autosage_status_t autosage_last_decision(autosage_handle_t h, char* json_buf, si
 autosage_status_t autosage_cache_load(autosage_handle_t h, const char* path);
 autosage_status_t autosage_cache_save(autosage_handle_t h, const char* path);
 autosage_status_t autosage_cache_clear(autosage_handle_t h);
-/* Direct access for tests and tools (host only). found = 0/1. */
-autosage_status_t autosage_cache_lookup(autosage_handle_t h, uint64_t graph_sig, int32_t F, autosage_op_t op,
-                                        autosage_dtype_t dt, autosage_schedule_t* sched, int32_t* found);
-autosage_status_t autosage_cache_insert(autosage_handle_t h, uint64_t graph_sig, int32_t F, autosage_op_t op,
-                                        autosage_dtype_t dt, const autosage_schedule_t* sched);
+/* Direct access for tests and tools (host only). found = 0/1.  F = feature width (attention: d),
+ * H = heads (1 for SpMM / SDDMM). */
+autosage_status_t autosage_cache_lookup(autosage_handle_t h, uint64_t graph_sig, int32_t F, int32_t H,
+                                        autosage_op_t op, autosage_dtype_t dt, autosage_schedule_t* sched,
+                                        int32_t* found);
+autosage_status_t autosage_cache_insert(autosage_handle_t h, uint64_t graph_sig, int32_t F, int32_t H,
+                                        autosage_op_t op, autosage_dtype_t dt, const autosage_schedule_t* sched);
 
 /* Telemetry (Contributions: deployment toggles and telemetry).  Between profile_begin and
  * profile_read every kernel stage the handle launches is bracketed by a pair of HIP events on its

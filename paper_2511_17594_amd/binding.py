@@ -68,8 +68,9 @@ def _load():
         "autosage_cache_load": [vp, c.c_char_p],
         "autosage_cache_save": [vp, c.c_char_p],
         "autosage_cache_clear": [vp],
-        "autosage_cache_lookup": [vp, c.c_uint64, i32, c.c_int, c.c_int, sp, c.POINTER(i32)],
-        "autosage_cache_insert": [vp, c.c_uint64, i32, c.c_int, c.c_int, sp],
+        "autosage_cache_lookup": [vp, c.c_uint64, i32, i32, c.c_int, c.c_int, sp, c.POINTER(i32)],
+        "autosage_cache_insert": [vp, c.c_uint64, i32, i32, c.c_int, c.c_int, sp],
+        "autosage_decide_attention": [vp, i64, i64, vp, vp, vp, vp, vp, vp, i32, i32, c.c_float, c.c_int, vp, sz, vp, sp],
         "autosage_baseline_schedule": [sp],
         "autosage_profile_begin": [vp],
         "autosage_profile_read": [vp, c.c_char_p, sz],
@@ -249,6 +250,16 @@ class Handle:
                "autosage_decide")
         return chosen
 
+    def decide_attention(self, N, rowptr, colind, Q, K, V, O, H, d, scale, dt=BF16, workspace=None, stream=None,
+                         nnz=None) -> Schedule:
+        nnz = int(colind.numel()) if nnz is None else nnz
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        chosen = Schedule()
+        _check(_lib.autosage_decide_attention(self._h, N, nnz, _ptr(rowptr), _ptr(colind), _ptr(Q), _ptr(K), _ptr(V),
+                                              _ptr(O), H, d, float(scale), dt, _ptr(workspace), ws_bytes,
+                                              _stream(stream), ctypes.byref(chosen)), "autosage_decide_attention")
+        return chosen
+
     def last_decision(self) -> dict:
         buf = ctypes.create_string_buffer(1 << 16)
         _check(_lib.autosage_last_decision(self._h, buf, len(buf)), "autosage_last_decision")
@@ -271,11 +282,11 @@ class Handle:
     def cache_clear(self):
         _check(_lib.autosage_cache_clear(self._h), "autosage_cache_clear")
 
-    def cache_lookup(self, graph_sig: int, F: int, op: int, dt: int = F32) -> Optional[Schedule]:
+    def cache_lookup(self, graph_sig: int, F: int, op: int, dt: int = F32, H: int = 1) -> Optional[Schedule]:
         s, found = Schedule(), ctypes.c_int32()
-        _check(_lib.autosage_cache_lookup(self._h, graph_sig, F, op, dt, ctypes.byref(s), ctypes.byref(found)),
+        _check(_lib.autosage_cache_lookup(self._h, graph_sig, F, H, op, dt, ctypes.byref(s), ctypes.byref(found)),
                "autosage_cache_lookup")
         return s if found.value else None
 
-    def cache_insert(self, graph_sig: int, F: int, op: int, dt: int, sched: Schedule):
-        _check(_lib.autosage_cache_insert(self._h, graph_sig, F, op, dt, ctypes.byref(sched)), "autosage_cache_insert")
+    def cache_insert(self, graph_sig: int, F: int, op: int, dt: int, sched: Schedule, H: int = 1):
+        _check(_lib.autosage_cache_insert(self._h, graph_sig, F, H, op, dt, ctypes.byref(sched)), "autosage_cache_insert")

@@ -584,57 +584,47 @@ extern "C" autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64
 static size_t attention_part_floats(int32_t H, int32_t d) { return (size_t)H * d > 2 * (size_t)H ? (size_t)H * d : 2 * (size_t)H; }
 
 // Which attention pipeline a schedule asks for: 1 = single pass, 0 = three stages, -1 = cannot run.
-static int attention_pipeline(const autosage_schedule_t* sched, int32_t H, int32_t d, int dt, AttnShape* shape)
+static int attention_pipeline(const autosage_schedule_t& sched, int32_t H, int32_t d, int dt, AttnShape* shape)
 {
     const bool can_fuse = attn_fused_shape(H, d, dt, shape);
-    const int mapping = sched ? sched->mapping : AUTOSAGE_MAP_PLAIN;
-    if (mapping == AUTOSAGE_MAP_FUSED) return can_fuse ? 1 : -1;
-    if (mapping == AUTOSAGE_MAP_WAVE_ROW) return 0;
-    if (mapping == AUTOSAGE_MAP_PLAIN) return can_fuse ? 1 : 0;        // library default
+    if (sched.mapping == AUTOSAGE_MAP_FUSED) return can_fuse ? 1 : -1;
+    if (sched.mapping == AUTOSAGE_MAP_WAVE_ROW || sched.mapping == AUTOSAGE_MAP_PLAIN) return 0;
     return -1;
 }
 
-extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t N, int64_t nnz,
-                                                    const int32_t* rowptr, const int32_t* colind, const float* val,
-                                                    const void* Q, const void* K, const void* V, float* O,
-                                                    int32_t H, int32_t d, float scale, autosage_dtype_t in_dt,
-                                                    const autosage_schedule_t* sched,
-                                                    void* workspace, size_t workspace_bytes, void* stream)
-{
-    (void)val;
-    if (!h || !sizes_ok(N, N, nnz) || H <= 0 || d <= 0 || (int64_t)H * d >= (1 << 24)) return AUTOSAGE_ERR_INVALID_ARG;
-    if (in_dt != AUTOSAGE_F32 && in_dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
-    if (!rowptr || !O || (nnz > 0 && (!colind || !Q || !K || !V))) return AUTOSAGE_ERR_INVALID_ARG;
-    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
-    if (N == 0) return AUTOSAGE_OK;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int esize = in_dt == AUTOSAGE_BF16 ? 2 : 4;
-    const int64_t HD = (int64_t)H * d;
-    // 16-byte lane loads are required: d must be a multiple of 16 / esize elements and the operands aligned
-    if ((d * esize) % 16 != 0) return AUTOSAGE_ERR_UNSUPPORTED;
-    int al = common_alignment(Q, HD, esize);
-    int t = common_alignment(K, HD, esize);
-    if (t < al) al = t;
-    t = common_alignment(V, HD, esize);
-    if (t < al) al = t;
-    if (al < 16 || common_alignment(O, HD, 4) < 16) return AUTOSAGE_ERR_UNSUPPORTED;
+namespace autosage {
 
-    autosage_schedule_t s{};
-    if (sched) s = *sched;
-    else {
-        s.hub_t = 512;
-        s.hub_chunk = 512;
-    }
+autosage_status_t attention_alignment(const AttnCall& c)
+{
+    const int esize = c.dt == AUTOSAGE_BF16 ? 2 : 4;
+    const int64_t HD = (int64_t)c.H * c.d;
+    // 16-byte lane loads are required: d must be a multiple of 16 / esize elements and the operands aligned
+    if ((c.d * esize) % 16 != 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    int al = common_alignment(c.Q, HD, esize);
+    al = std::min(al, common_alignment(c.K, HD, esize));
+    al = std::min(al, common_alignment(c.V, HD, esize));
+    if (al < 16 || common_alignment(c.O, HD, 4) < 16) return AUTOSAGE_ERR_UNSUPPORTED;
+    return AUTOSAGE_OK;
+}
+
+autosage_status_t exec_attention(autosage_ctx* h, const AttnCall& c, const autosage_schedule_t& sched, const RowMap& rows,
+                                 void* workspace, size_t workspace_bytes, hipStream_t st)
+{
+    if (rows.count == 0) return AUTOSAGE_OK;
+    const int32_t H = c.H, d = c.d;
+    const int64_t HD = (int64_t)H * d;
+    const int64_t nnz = c.nnz;
+    autosage_schedule_t s = sched;
     AttnShape shape{};
-    const int pipeline = attention_pipeline(sched, H, d, in_dt, &shape);
+    const int pipeline = attention_pipeline(sched, H, d, c.dt, &shape);
     if (pipeline < 0) return AUTOSAGE_ERR_UNSUPPORTED;
     s.mapping = AUTOSAGE_MAP_WAVE_ROW;
     s.f_tile = 0;
     s.vec_bytes = 16;
     Resolved rs, rp;
-    autosage_status_t rc = resolve_schedule(s, AUTOSAGE_OP_SDDMM, d, in_dt, H, al, 16, &rs);
+    autosage_status_t rc = resolve_schedule(s, AUTOSAGE_OP_SDDMM, d, c.dt, H, 16, 16, &rs);
     if (rc != AUTOSAGE_OK) return rc;
-    rc = resolve_schedule(s, AUTOSAGE_OP_SPMM, (int32_t)HD, in_dt, 1, al, 16, &rp);
+    rc = resolve_schedule(s, AUTOSAGE_OP_SPMM, (int32_t)HD, c.dt, 1, 16, 16, &rp);
     if (rc != AUTOSAGE_OK) return rc;
 
     if (pipeline == 1) {
@@ -643,24 +633,24 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
         shape.hub_t = rs.hub_t;
         shape.hub_chunk = rs.hub_chunk;
         AttnArgs fa{};
-        fa.rows = RowMap{0, 1, (int32_t)N, 0};
-        fa.rowptr = rowptr;
-        fa.colind = colind;
-        fa.Q = Q;
-        fa.K = K;
-        fa.V = V;
-        fa.O = O;
+        fa.rows = rows;
+        fa.rowptr = c.rowptr;
+        fa.colind = c.colind;
+        fa.Q = c.Q;
+        fa.K = c.K;
+        fa.V = c.V;
+        fa.O = c.O;
         fa.H = H;
         fa.d = d;
-        fa.dt = in_dt;
-        fa.scale = scale;
+        fa.dt = c.dt;
+        fa.scale = c.scale;
         HubMeta fmeta{};
         float* fpart = nullptr;
         if (shape.hub_t > 0) {
-            if (!carve_hub(workspace, workspace_bytes, N, nnz, shape.hub_t, shape.hub_chunk,
+            if (!carve_hub(workspace, workspace_bytes, rows.count, nnz, shape.hub_t, shape.hub_chunk,
                            (int64_t)attn_fused_part_floats(shape), &fmeta, &fpart, nullptr))
                 return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
-            STAGE(h, "hub_partition", st, launch_hub_partition(fa.rows, rowptr, shape.hub_t, shape.hub_chunk, fmeta, st));
+            STAGE(h, "hub_partition", st, launch_hub_partition(rows, c.rowptr, shape.hub_t, shape.hub_chunk, fmeta, st));
         }
         STAGE(h, "attn_fused_rows", st, launch_attn_fused_rows(fa, shape, st));
         if (shape.hub_t > 0) STAGE(h, "attn_fused_hub", st, launch_attn_fused_hub(fa, shape, fmeta, fpart, st));
@@ -674,29 +664,28 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
     char* hub_ws = static_cast<char*>(workspace) + score_bytes;
     const size_t hub_ws_bytes = workspace_bytes - score_bytes;
 
-    const RowMap rows{0, 1, (int32_t)N, 0};
     HubMeta meta{};
     float* part = nullptr;
     if (rs.hub_t > 0) {
-        if (!carve_hub(hub_ws, hub_ws_bytes, N, nnz, rs.hub_t, rs.hub_chunk, (int64_t)attention_part_floats(H, d), &meta,
-                       &part, nullptr))
+        if (!carve_hub(hub_ws, hub_ws_bytes, rows.count, nnz, rs.hub_t, rs.hub_chunk, (int64_t)attention_part_floats(H, d),
+                       &meta, &part, nullptr))
             return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
-        STAGE(h, "hub_partition", st, launch_hub_partition(rows, rowptr, rs.hub_t, rs.hub_chunk, meta, st));
+        STAGE(h, "hub_partition", st, launch_hub_partition(rows, c.rowptr, rs.hub_t, rs.hub_chunk, meta, st));
     }
     // stage 1: scores
     SddmmArgs sa{};
     sa.rows = rows;
-    sa.rowptr = rowptr;
-    sa.colind = colind;
-    sa.X = Q;
+    sa.rowptr = c.rowptr;
+    sa.colind = c.colind;
+    sa.X = c.Q;
     sa.ldx = HD;
-    sa.Y = K;
+    sa.Y = c.K;
     sa.ldy = HD;
     sa.out = S;
     sa.F = d;
-    sa.dt = in_dt;
+    sa.dt = c.dt;
     sa.heads = H;
-    sa.scale = scale;
+    sa.scale = c.scale;
     if (nnz > 0) {
         STAGE(h, "attn_sddmm_rows", st, launch_sddmm_rows(sa, rs, st));
         if (rs.hub_t > 0) STAGE(h, "attn_sddmm_hub", st, launch_sddmm_hub(sa, rs, meta, st));
@@ -704,7 +693,7 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
     // stage 2: row-softmax in place
     SoftmaxArgs ma{};
     ma.rows = rows;
-    ma.rowptr = rowptr;
+    ma.rowptr = c.rowptr;
     ma.in = S;
     ma.out = S;
     ma.H = H;
@@ -713,20 +702,49 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
     // stage 3: weighted sum of V rows with per-head weights
     SpmmArgs pa{};
     pa.rows = rows;
-    pa.rowptr = rowptr;
-    pa.colind = colind;
+    pa.rowptr = c.rowptr;
+    pa.colind = c.colind;
     pa.val = S;
-    pa.B = V;
+    pa.B = c.V;
     pa.ldb = HD;
-    pa.C = O;
+    pa.C = c.O;
     pa.ldc = HD;
     pa.F = (int32_t)HD;
-    pa.dt = in_dt;
+    pa.dt = c.dt;
     pa.heads = H > 1 ? H : 1;
     pa.head_dim = d;
     STAGE(h, "attn_spmm_rows", st, launch_spmm_rows(pa, rp, st));
     if (rp.hub_t > 0) STAGE(h, "attn_spmm_hub", st, launch_spmm_hub(pa, rp, meta, part, st));
     return AUTOSAGE_OK;
+}
+
+}  // namespace autosage
+
+extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t N, int64_t nnz,
+                                                    const int32_t* rowptr, const int32_t* colind, const float* val,
+                                                    const void* Q, const void* K, const void* V, float* O,
+                                                    int32_t H, int32_t d, float scale, autosage_dtype_t in_dt,
+                                                    const autosage_schedule_t* sched,
+                                                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)val;
+    if (!h || !sizes_ok(N, N, nnz) || H <= 0 || d <= 0 || (int64_t)H * d >= (1 << 24)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (in_dt != AUTOSAGE_F32 && in_dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (N == 0) return AUTOSAGE_OK;
+    if (!rowptr || !O || (nnz > 0 && (!colind || !Q || !K || !V))) return AUTOSAGE_ERR_INVALID_ARG;
+    AttnCall c{N, nnz, rowptr, colind, Q, K, V, O, H, d, scale, (int)in_dt};
+    autosage_status_t rc = attention_alignment(c);
+    if (rc != AUTOSAGE_OK) return rc;
+    autosage_schedule_t chosen;
+    if (!sched) {
+        rc = autosage_decide_attention(h, N, nnz, rowptr, colind, Q, K, V, O, H, d, scale, in_dt, workspace,
+                                       workspace_bytes, stream, &chosen);
+        if (rc != AUTOSAGE_OK) return rc;
+        sched = &chosen;
+    }
+    return exec_attention(h, c, *sched, RowMap{0, 1, (int32_t)N, 0}, workspace, workspace_bytes,
+                          static_cast<hipStream_t>(stream));
 }
 
 extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autosage_op_t op, int64_t n_rows,
@@ -740,7 +758,7 @@ extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autos
         chunk = sched->hub_t > 0 ? (sched->hub_chunk > 0 ? sched->hub_chunk : sched->hub_t) : 0;
         if (hub_t < 0 || (hub_t > 0 && (hub_t < kMinHubT || chunk < kMinHubT))) return AUTOSAGE_ERR_INVALID_ARG;
     } else if (op == AUTOSAGE_OP_ATTENTION) {
-        hub_t = chunk = 512;
+        hub_t = chunk = 256;               // smallest threshold the attention selector proposes
     }
     size_t b = 0;
     switch (op) {
@@ -756,10 +774,9 @@ extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autos
             const size_t three = align_up(sizeof(float) * (size_t)nnz * H, 256) +
                                  hub_workspace_bytes(n_rows, nnz, hub_t, chunk, (int64_t)attention_part_floats(H, F));
             const size_t fused = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, (int64_t)fused_floats);
-            const int mapping = sched ? sched->mapping : AUTOSAGE_MAP_PLAIN;
-            if (mapping == AUTOSAGE_MAP_FUSED) b = fused;
-            else if (mapping == AUTOSAGE_MAP_WAVE_ROW) b = three;
-            else b = std::max(three, fused);
+            if (!sched) b = std::max(three, fused);
+            else if (sched->mapping == AUTOSAGE_MAP_FUSED) b = fused;
+            else b = three;
             break;
         }
         default: return AUTOSAGE_ERR_INVALID_ARG;

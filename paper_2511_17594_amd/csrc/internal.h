@@ -15,13 +15,28 @@ namespace autosage {
 
 struct CacheKey {
     uint64_t graph_sig;
-    int32_t F;
+    int32_t F;      // feature width (attention: head width d)
+    int32_t H;      // heads (1 for SpMM / SDDMM)
     int32_t op;
     int32_t dt;
     bool operator<(const CacheKey& o) const
     {
-        return std::tie(graph_sig, F, op, dt) < std::tie(o.graph_sig, o.F, o.op, o.dt);
+        return std::tie(graph_sig, F, H, op, dt) < std::tie(o.graph_sig, o.F, o.H, o.op, o.dt);
     }
+};
+
+// One CSR-attention call (device pointers).
+struct AttnCall {
+    int64_t N, nnz;
+    const int32_t* rowptr;
+    const int32_t* colind;
+    const void* Q;
+    const void* K;
+    const void* V;
+    float* O;
+    int32_t H, d;
+    float scale;
+    int dt;
 };
 
 struct CacheEntry {
@@ -110,6 +125,12 @@ autosage_status_t exec_spmm(autosage_ctx* h, const SpmmArgs& a, const Resolved& 
                             hipStream_t st);
 autosage_status_t exec_sddmm(autosage_ctx* h, const SddmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes,
                              hipStream_t st);
+
+// Checks the 16-byte alignment / width rules of the attention kernels.
+autosage_status_t attention_alignment(const AttnCall& c);
+// Runs the attention pipeline the schedule names (FUSED = single pass, else three stages) on `rows`.
+autosage_status_t exec_attention(autosage_ctx* h, const AttnCall& c, const autosage_schedule_t& sched, const RowMap& rows,
+                                 void* workspace, size_t workspace_bytes, hipStream_t st);
 
 // Brackets one kernel stage with a pair of events on its stream while profiling is on.
 class StageTimer {

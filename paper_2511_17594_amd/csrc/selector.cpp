@@ -229,26 +229,27 @@ extern "C" autosage_status_t autosage_cache_clear(autosage_handle_t h)
     return AUTOSAGE_OK;
 }
 
-extern "C" autosage_status_t autosage_cache_lookup(autosage_handle_t h, uint64_t graph_sig, int32_t F, autosage_op_t op,
-                                                   autosage_dtype_t dt, autosage_schedule_t* sched, int32_t* found)
+extern "C" autosage_status_t autosage_cache_lookup(autosage_handle_t h, uint64_t graph_sig, int32_t F, int32_t H,
+                                                   autosage_op_t op, autosage_dtype_t dt, autosage_schedule_t* sched,
+                                                   int32_t* found)
 {
     if (!h || !found) return AUTOSAGE_ERR_INVALID_ARG;
-    auto it = h->cache.find(CacheKey{graph_sig, F, (int32_t)op, (int32_t)dt});
+    auto it = h->cache.find(CacheKey{graph_sig, F, H, (int32_t)op, (int32_t)dt});
     *found = it != h->cache.end();
     if (*found && sched) *sched = it->second.sched;
     return AUTOSAGE_OK;
 }
 
-extern "C" autosage_status_t autosage_cache_insert(autosage_handle_t h, uint64_t graph_sig, int32_t F, autosage_op_t op,
-                                                   autosage_dtype_t dt, const autosage_schedule_t* sched)
+extern "C" autosage_status_t autosage_cache_insert(autosage_handle_t h, uint64_t graph_sig, int32_t F, int32_t H,
+                                                   autosage_op_t op, autosage_dtype_t dt, const autosage_schedule_t* sched)
 {
-    if (!h || !sched) return AUTOSAGE_ERR_INVALID_ARG;
-    h->cache[CacheKey{graph_sig, F, (int32_t)op, (int32_t)dt}] = CacheEntry{*sched, 0.0, 0.0};
+    if (!h || !sched || F <= 0 || H <= 0) return AUTOSAGE_ERR_INVALID_ARG;
+    h->cache[CacheKey{graph_sig, F, H, (int32_t)op, (int32_t)dt}] = CacheEntry{*sched, 0.0, 0.0};
     return AUTOSAGE_OK;
 }
 
 // One record per line:
-//   autosage-cache-v1 <device_sig> <graph_sig hex> <F> <op> <dt> <mapping> <f_tile> <wpg> <vec_bytes> <unroll>
+//   autosage-cache-v2 <device_sig> <graph_sig hex> <F> <H> <op> <dt> <mapping> <f_tile> <wpg> <vec_bytes> <unroll>
 //   <hub_t> <hub_chunk> <xcd_remap> <t_baseline_ms> <t_chosen_ms>
 // Records of another device signature are kept out of the in-memory cache (stale-reuse guard).
 extern "C" autosage_status_t autosage_cache_load(autosage_handle_t h, const char* path)
@@ -263,14 +264,14 @@ extern "C" autosage_status_t autosage_cache_load(autosage_handle_t h, const char
         CacheKey k{};
         CacheEntry e{};
         autosage_schedule_t& s = e.sched;
-        if (!(ss >> tag >> dev >> sig_hex >> k.F >> k.op >> k.dt >> s.mapping >> s.f_tile >> s.waves_per_wg >> s.vec_bytes >>
+        if (!(ss >> tag >> dev >> sig_hex >> k.F >> k.H >> k.op >> k.dt >> s.mapping >> s.f_tile >> s.waves_per_wg >> s.vec_bytes >>
               s.unroll >> s.hub_t >> s.hub_chunk >> s.xcd_remap >> e.t_baseline_ms >> e.t_chosen_ms))
             continue;
-        if (tag != "autosage-cache-v1" || dev != h->device_sig) continue;
+        if (tag != "autosage-cache-v2" || dev != h->device_sig) continue;
         char* end = nullptr;
         k.graph_sig = std::strtoull(sig_hex.c_str(), &end, 16);
         if (end == sig_hex.c_str() || *end != '\0') continue;
-        if (s.mapping < 0 || s.mapping > 2 || k.op < 0 || k.op > 3 || k.dt < 0 || k.dt > 1 || k.F <= 0) continue;
+        if (s.mapping < 0 || s.mapping > 3 || k.op < 0 || k.op > 3 || k.dt < 0 || k.dt > 1 || k.F <= 0 || k.H <= 0) continue;
         h->cache[k] = e;
     }
     return AUTOSAGE_OK;
@@ -287,8 +288,8 @@ extern "C" autosage_status_t autosage_cache_save(autosage_handle_t h, const char
             const CacheKey& k = kv.first;
             const autosage_schedule_t& s = kv.second.sched;
             char buf[512];
-            std::snprintf(buf, sizeof buf, "autosage-cache-v1 %s %016llx %d %d %d %d %d %d %d %d %d %d %d %.6f %.6f\n",
-                          h->device_sig.c_str(), (unsigned long long)k.graph_sig, k.F, k.op, k.dt, s.mapping, s.f_tile,
+            std::snprintf(buf, sizeof buf, "autosage-cache-v2 %s %016llx %d %d %d %d %d %d %d %d %d %d %d %d %.6f %.6f\n",
+                          h->device_sig.c_str(), (unsigned long long)k.graph_sig, k.F, k.H, k.op, k.dt, s.mapping, s.f_tile,
                           s.waves_per_wg, s.vec_bytes, s.unroll, s.hub_t, s.hub_chunk, s.xcd_remap,
                           kv.second.t_baseline_ms, kv.second.t_chosen_ms);
             out << buf;
@@ -328,6 +329,10 @@ struct OpInput {
     int64_t ld_out;
     int32_t F;
     int dt;
+    // attention only
+    const void* d2;
+    int32_t H;
+    float scale;
 };
 
 autosage_status_t run_once(autosage_ctx* h, const OpInput& in, const RowMap& rows, const autosage_schedule_t& s, void* ws, size_t ws_bytes,
@@ -335,6 +340,10 @@ autosage_status_t run_once(autosage_ctx* h, const OpInput& in, const RowMap& row
 {
     const int esize = in.dt == DT_BF16 ? 2 : 4;
     Resolved r;
+    if (in.op == AUTOSAGE_OP_ATTENTION) {
+        const AttnCall c{in.n_rows, in.nnz, in.rowptr, in.colind, in.d0, in.d1, in.d2, in.out, in.H, in.F, in.scale, in.dt};
+        return exec_attention(h, c, s, rows, ws, ws_bytes, st);
+    }
     if (in.op == AUTOSAGE_OP_SPMM) {
         autosage_status_t rc = resolve_schedule(s, in.op, in.F, in.dt, 1, common_alignment(in.d0, in.ld0, esize),
                                                 common_alignment(in.out, in.ld_out, 4), &r);
@@ -415,18 +424,59 @@ std::string num(double x)
 
 }  // namespace
 
-extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t op, int64_t n_rows, int64_t n_cols,
-                                             int64_t nnz, const int32_t* rowptr, const int32_t* colind, const float* val,
-                                             const void* dense0, int64_t ld0, const void* dense1, int64_t ld1,
-                                             float* out, int64_t ld_out, int32_t F, autosage_dtype_t dt,
-                                             void* workspace, size_t workspace_bytes, void* stream,
-                                             autosage_schedule_t* chosen)
+// Candidates of the attention pipeline: the single pass (when the head shape has kernels) and the three
+// stages, each over a few hub thresholds; ranked by gathered bytes, score traffic and the longest row.
+static void shortlist_attention(const autosage_ctx* h, int64_t nnz, const int64_t* hist, int64_t max_deg, int32_t H,
+                                int32_t d, int dt, std::vector<autosage_schedule_t>* out, std::vector<double>* est)
 {
-    if (!h || !chosen || !rowptr || F <= 0 || n_rows < 0 || nnz < 0) return AUTOSAGE_ERR_INVALID_ARG;
-    if (op != AUTOSAGE_OP_SPMM && op != AUTOSAGE_OP_SDDMM) return AUTOSAGE_ERR_INVALID_ARG;
-    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
-    if (nnz > 0 && (!colind || !dense0 || !out || (op == AUTOSAGE_OP_SPMM && !val) || (op == AUTOSAGE_OP_SDDMM && !dense1)))
-        return AUTOSAGE_ERR_INVALID_ARG;
+    const int esize = dt == DT_BF16 ? 2 : 4;
+    AttnShape shape{};
+    const bool can_fuse = attn_fused_shape(H, d, dt, &shape);
+    const double row_bytes = 2.0 * H * d * esize;                  // one K row and one V row per nonzero
+    const double bw = 6.0e12, t_step = 1.0e-6, t_launch = 6.0e-6;
+    std::vector<std::pair<double, autosage_schedule_t>> all;
+    const int hubs[] = {0, 256, 512, 1024, 2048};
+    for (int fused = 1; fused >= 0; --fused) {
+        if (fused && !can_fuse) continue;
+        for (int hub : hubs) {
+            if (hub > 0 && max_deg < hub) continue;
+            if (h->params.force_hub_t >= 0 && hub != hubs[0]) continue;
+            autosage_schedule_t s{};
+            s.mapping = fused ? AUTOSAGE_MAP_FUSED : AUTOSAGE_MAP_WAVE_ROW;
+            s.waves_per_wg = h->params.force_wpb > 0 ? h->params.force_wpb : 4;
+            s.hub_t = h->params.force_hub_t >= 0 ? h->params.force_hub_t : hub;
+            s.hub_chunk = s.hub_t;
+            double t = nnz * row_bytes / bw + (fused ? 0.0 : 16.0 * H * nnz / bw + 2 * t_launch);
+            const double longest = s.hub_t > 0 ? std::min<double>((double)max_deg, s.hub_t) : (double)max_deg;
+            t = std::max(t, longest / 4.0 * t_step * (fused ? 1.0 : 2.0));
+            if (s.hub_t > 0) {
+                int64_t hub_nnz = 0;
+                for (int b = 1; b < 33; ++b)
+                    if (std::ldexp(1.0, b - 1) >= s.hub_t) hub_nnz += (int64_t)(1.5 * std::ldexp(1.0, b - 1) * hist[b]);
+                t += (fused ? 3 : 7) * t_launch + 0.05 * hub_nnz * row_bytes / bw;   // chunked rows run a little slower
+            }
+            all.emplace_back(t, s);
+        }
+    }
+    std::stable_sort(all.begin(), all.end(), [](const auto& a, const auto& b) { return a.first < b.first; });
+    for (const auto& e : all) {
+        out->push_back(e.second);
+        est->push_back(e.first);
+    }
+}
+
+static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, void* workspace, size_t workspace_bytes,
+                                     void* stream, autosage_schedule_t* chosen)
+{
+    const autosage_op_t op = static_cast<autosage_op_t>(in.op);
+    const autosage_dtype_t dt = static_cast<autosage_dtype_t>(in.dt);
+    const int64_t n_rows = in.n_rows, n_cols = in.n_cols, nnz = in.nnz;
+    const int32_t* rowptr = in.rowptr;
+    const void* dense0 = in.d0;
+    const void* dense1 = in.d1;
+    const int64_t ld0 = in.ld0, ld1 = in.ld1, ld_out = in.ld_out;
+    float* out = in.out;
+    const int32_t F = in.F;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const auto wall0 = std::chrono::steady_clock::now();
 
@@ -468,11 +518,11 @@ extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t 
     std::ostringstream js;
     char sigbuf[32];
     std::snprintf(sigbuf, sizeof sigbuf, "%016llx", (unsigned long long)sig);
-    js << "{\"op\":" << (int)op << ",\"F\":" << F << ",\"dt\":" << (int)dt << ",\"graph_sig\":\"" << sigbuf
+    js << "{\"op\":" << (int)op << ",\"F\":" << F << ",\"H\":" << in.H << ",\"dt\":" << (int)dt << ",\"graph_sig\":\"" << sigbuf
        << "\",\"device_sig\":\"" << h->device_sig << "\",\"alpha\":" << num(h->params.alpha);
 
     // 2. cache
-    const CacheKey key{sig, F, (int32_t)op, (int32_t)dt};
+    const CacheKey key{sig, F, in.H, (int32_t)op, (int32_t)dt};
     auto it = h->cache.find(key);
     if (it != h->cache.end()) {
         *chosen = it->second.sched;
@@ -492,14 +542,15 @@ extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t 
     const int esize = dt == AUTOSAGE_BF16 ? 2 : 4;
     int al = common_alignment(dense0, ld0, esize);
     if (op == AUTOSAGE_OP_SDDMM) al = std::min(al, common_alignment(dense1, ld1, esize));
-    else al = std::min(al, common_alignment(out, ld_out, 4));
+    else if (op == AUTOSAGE_OP_SPMM) al = std::min(al, common_alignment(out, ld_out, 4));
     std::vector<autosage_schedule_t> cands;
     std::vector<double> est;
     {
         // the probes get the best-ranked candidates that differ in more than the unroll depth
         std::vector<autosage_schedule_t> all;
         std::vector<double> all_est;
-        shortlist(h, op, n_rows, n_cols, nnz, hist, max_deg, F, dt, al, &all, &all_est);
+        if (op == AUTOSAGE_OP_ATTENTION) shortlist_attention(h, nnz, hist, max_deg, in.H, F, dt, &all, &all_est);
+        else shortlist(h, op, n_rows, n_cols, nnz, hist, max_deg, F, dt, al, &all, &all_est);
         for (size_t i = 0; i < all.size() && (int)cands.size() < h->params.probe_topk; ++i) {
             bool fresh = true;
             for (const autosage_schedule_t& c : cands)
@@ -530,7 +581,6 @@ extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t 
             sample = RowMap{(int32_t)((stride - block) / 2), (int32_t)stride, (int32_t)(nb * block), shift};
         }
     }
-    OpInput in{(int)op, n_rows, n_cols, nnz, rowptr, colind, val, dense0, ld0, dense1, ld1, out, ld_out, F, (int)dt};
 
     const double tb = time_schedule(h, in, sample, base, workspace, workspace_bytes, st, h->params.probe_iters,
                                     h->params.probe_cap_ms);
@@ -572,4 +622,40 @@ extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t 
     js << ",\"choice\":" << schedule_json(*chosen) << ",\"probe_wall_ms\":" << num(wall_ms) << "}";
     h->last_decision = js.str();
     return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t op, int64_t n_rows, int64_t n_cols,
+                                             int64_t nnz, const int32_t* rowptr, const int32_t* colind, const float* val,
+                                             const void* dense0, int64_t ld0, const void* dense1, int64_t ld1,
+                                             float* out, int64_t ld_out, int32_t F, autosage_dtype_t dt,
+                                             void* workspace, size_t workspace_bytes, void* stream,
+                                             autosage_schedule_t* chosen)
+{
+    if (!h || !chosen || !rowptr || F <= 0 || n_rows < 0 || nnz < 0) return AUTOSAGE_ERR_INVALID_ARG;
+    if (op != AUTOSAGE_OP_SPMM && op != AUTOSAGE_OP_SDDMM) return AUTOSAGE_ERR_INVALID_ARG;
+    if (dt != AUTOSAGE_F32 && dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (nnz > 0 && (!colind || !dense0 || !out || (op == AUTOSAGE_OP_SPMM && !val) || (op == AUTOSAGE_OP_SDDMM && !dense1)))
+        return AUTOSAGE_ERR_INVALID_ARG;
+    OpInput in{(int)op, n_rows, n_cols, nnz, rowptr, colind, val, dense0, ld0, dense1, ld1, out, ld_out, F, (int)dt,
+               nullptr, 1, 1.0f};
+    return decide_impl(h, in, workspace, workspace_bytes, stream, chosen);
+}
+
+extern "C" autosage_status_t autosage_decide_attention(autosage_handle_t h, int64_t N, int64_t nnz, const int32_t* rowptr,
+                                                       const int32_t* colind, const void* Q, const void* K, const void* V,
+                                                       float* O, int32_t H, int32_t d, float scale, autosage_dtype_t dt,
+                                                       void* workspace, size_t workspace_bytes, void* stream,
+                                                       autosage_schedule_t* chosen)
+{
+    if (!h || !chosen || !rowptr || H <= 0 || d <= 0 || N < 0 || nnz < 0) return AUTOSAGE_ERR_INVALID_ARG;
+    if (dt != AUTOSAGE_F32 && dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (!O || (nnz > 0 && (!colind || !Q || !K || !V))) return AUTOSAGE_ERR_INVALID_ARG;
+    const AttnCall c{N, nnz, rowptr, colind, Q, K, V, O, H, d, scale, (int)dt};
+    autosage_status_t rc = attention_alignment(c);
+    if (rc != AUTOSAGE_OK) return rc;
+    const int64_t HD = (int64_t)H * d;
+    OpInput in{AUTOSAGE_OP_ATTENTION, N, N, nnz, rowptr, colind, nullptr, Q, HD, K, HD, O, HD, d, (int)dt, V, H, scale};
+    return decide_impl(h, in, workspace, workspace_bytes, stream, chosen);
 }

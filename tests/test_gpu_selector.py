@@ -142,3 +142,34 @@ def test_guardrail_falls_back_when_alpha_is_unreachable(torch, ab, graph):
     d = h.last_decision()
     assert d["choice_index"] == -1 and s.mapping == ab.MAP_PLAIN and s.as_dict() == ab.baseline_schedule().as_dict()
     h.close()
+
+
+def test_attention_decision(torch, ab, graph):
+    A, H, d = graph, 4, 32
+    Q, K, V = W.config5_attention(A.n_rows, H, d, seed=3, qk_std=1.0)
+    h = ab.Handle(0)
+    rp, ci, dQ, dK, dV = (dev(t, torch) for t in (A.rowptr, A.colind, Q, K, V))
+    O = torch.full((A.n_rows, H, d), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(h.workspace_bytes(ab.OP_ATTENTION, A.n_rows, A.nnz, d, H), dtype=torch.uint8, device="cuda")
+    scale = d ** -0.5
+    s1 = h.decide_attention(A.n_rows, rp, ci, dQ, dK, dV, O, H, d, scale, workspace=ws)
+    d1 = h.last_decision()
+    assert d1["cache_hit"] is False and d1["op"] == ab.OP_ATTENTION and d1["H"] == H and d1["F"] == d
+    kinds = {c["sched"]["mapping"] for c in d1["candidates"]}
+    assert ab.MAP_FUSED in kinds                                     # the single pass is among the probed candidates
+    t = [c["t_ms"] if c["t_ms"] is not None else float("inf") for c in d1["candidates"]]
+    assert d1["choice_index"] == oracle.decide(t, d1["t_baseline_ms"], d1["alpha"])
+    assert s1.mapping in (ab.MAP_FUSED, ab.MAP_WAVE_ROW) and s1.hub_t > 0     # 8192-long rows: never the unsplit baseline
+    # the compute call with sched = NULL replays the decision and matches the oracle
+    h.csr_attention(A.n_rows, rp, ci, dQ, dK, dV, O, H, d, scale, workspace=ws)
+    assert h.last_decision()["cache_hit"] is True
+    torch.cuda.synchronize()
+    ref = oracle.csr_attention(A.rowptr, A.colind, Q, K, V, scale)
+    err = rel_l1_rows(O.cpu().numpy().reshape(-1, d), ref.reshape(-1, d))
+    assert err.max() <= 2e-2
+    # another head count is another key
+    Q2, K2, V2 = W.config5_attention(A.n_rows, 2, d, seed=4)
+    O2 = torch.empty((A.n_rows, 2, d), dtype=torch.float32, device="cuda")
+    h.decide_attention(A.n_rows, rp, ci, dev(Q2, torch), dev(K2, torch), dev(V2, torch), O2, 2, d, scale, workspace=ws)
+    assert h.last_decision()["cache_hit"] is False
+    h.close()

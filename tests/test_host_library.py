@@ -122,6 +122,10 @@ def test_cache_round_trip_and_corrupt_file(ab, host, tmp_path):
     s.mapping, s.vec_bytes, s.hub_t, s.hub_chunk, s.unroll, s.waves_per_wg = ab.MAP_WAVE_ROW, 16, 1024, 512, 4, 4
     host.cache_insert(0xDEADBEEF12345678, 64, ab.OP_SPMM, ab.F32, s)
     host.cache_insert(42, 128, ab.OP_SDDMM, ab.BF16, ab.baseline_schedule())
+    fused = ab.Schedule(mapping=ab.MAP_FUSED, hub_t=512, hub_chunk=512, waves_per_wg=4)
+    host.cache_insert(42, 64, ab.OP_ATTENTION, ab.BF16, fused, H=8)
+    assert host.cache_lookup(42, 64, ab.OP_ATTENTION, ab.BF16, H=8).mapping == ab.MAP_FUSED
+    assert host.cache_lookup(42, 64, ab.OP_ATTENTION, ab.BF16, H=4) is None         # heads are part of the key
     assert host.cache_lookup(0xDEADBEEF12345678, 64, ab.OP_SPMM, ab.F32).as_dict() == s.as_dict()
     assert host.cache_lookup(0xDEADBEEF12345678, 64, ab.OP_SDDMM, ab.F32) is None   # op is part of the key
     assert host.cache_lookup(0xDEADBEEF12345678, 32, ab.OP_SPMM, ab.F32) is None    # so is F
@@ -132,6 +136,7 @@ def test_cache_round_trip_and_corrupt_file(ab, host, tmp_path):
     h2.cache_load(path)
     assert h2.cache_lookup(0xDEADBEEF12345678, 64, ab.OP_SPMM, ab.F32).as_dict() == s.as_dict()
     assert h2.cache_lookup(42, 128, ab.OP_SDDMM, ab.BF16).mapping == ab.MAP_PLAIN
+    assert h2.cache_lookup(42, 64, ab.OP_ATTENTION, ab.BF16, H=8).as_dict() == fused.as_dict()
     # records of another device signature, truncated and garbage lines are skipped, good lines still load
     lines = open(path).read().splitlines()
     with open(path, "w") as f:
@@ -139,6 +144,7 @@ def test_cache_round_trip_and_corrupt_file(ab, host, tmp_path):
         f.write(lines[0][: len(lines[0]) // 2] + "\n")
         f.write(lines[0].replace(" host ", " some_other_gpu ") + "\n")
         f.write(lines[1] + "\n")
+        f.write(lines[1].replace("autosage-cache-v2", "autosage-cache-v1") + "\n")      # records of an older schema are skipped
     h3 = ab.Handle(-1)
     h3.cache_load(path)
     found = [h3.cache_lookup(0xDEADBEEF12345678, 64, ab.OP_SPMM, ab.F32), h3.cache_lookup(42, 128, ab.OP_SDDMM, ab.BF16)]
@@ -170,4 +176,4 @@ def test_env_toggles_are_read_at_creation(ab, monkeypatch, tmp_path):
     assert c and all(s.hub_t == 2048 for s, _ in c)
     h.cache_insert(7, 64, ab.OP_SPMM, ab.F32, ab.baseline_schedule())
     h.close()                                               # AUTOSAGE_CACHE is written on destroy
-    assert os.path.exists(path) and "autosage-cache-v1" in open(path).read()
+    assert os.path.exists(path) and "autosage-cache-v2" in open(path).read()
