@@ -4,7 +4,7 @@
 
 For every width: the selector's choice (cold call, then steady state from its cache), time (median of
 `--iters` HIP-event timings), GFLOP/s = 2*nnz*F/t, algorithmic GB/s (every gathered dense row counted
-once per nonzero) and its fraction of the 8 TB/s HBM peak, and the guardrail's fallback kernel on the
+once per nonzero; `--dtype bf16` halves the bytes of a gathered row) and its fraction of the 8 TB/s HBM peak, and the guardrail's fallback kernel on the
 same input.  `--vendor` adds the vendor SpMM reached through torch.sparse.mm.  Workloads: config1..4
 (the benchmark configurations), er (Erdos-Renyi N = 200000, p = 2e-5, the shape of the paper's
 extreme-sparsity stressor) and hubsplit_5k / hubsplit_12k (N = 20000, a few rows of degree 5000 /
@@ -53,6 +53,7 @@ def main(argv=None):
     ap.add_argument("--iters", type=int, default=10)
     ap.add_argument("--vendor", action="store_true")
     ap.add_argument("--no-sddmm", action="store_true")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="element type of the dense input operands")
     args = ap.parse_args(argv)
 
     import torch
@@ -95,13 +96,18 @@ def main(argv=None):
         g = torch.Generator(device="cuda").manual_seed(F)
         B = torch.randn((M, F), device="cuda", generator=g)
         X = torch.randn((N, F), device="cuda", generator=g)
+        if args.dtype == "bf16":
+            B, X = B.to(torch.bfloat16), X.to(torch.bfloat16)
         C = torch.empty((N, F), device="cuda")
         out = torch.empty(max(nnz, 1), device="cuda")
         ws = torch.empty(h.workspace_bytes(ab.OP_SPMM, N, nnz, F), dtype=torch.uint8, device="cuda")
-        bg = 4 * (N + 1) + 8 * nnz + nnz * F * 4 + N * F * 4
-        ops = [("SpMM", lambda s: h.spmm(N, M, rp, ci, va, B, C, F, sched=s, workspace=ws, stream=stream))]
+        esz = 2 if args.dtype == "bf16" else 4
+        dt = ab.BF16 if args.dtype == "bf16" else ab.F32
+        bg = 4 * (N + 1) + 8 * nnz + nnz * F * esz + N * F * 4
+        ops = [("SpMM", lambda s: h.spmm(N, M, rp, ci, va, B, C, F, dt=dt, sched=s, workspace=ws, stream=stream))]
         if not args.no_sddmm:
-            ops.append(("SDDMM", lambda s: h.sddmm(N, M, rp, ci, X, B, out, F, sched=s, workspace=ws, stream=stream, nnz=nnz)))
+            ops.append(("SDDMM", lambda s: h.sddmm(N, M, rp, ci, X, B, out, F, dt=dt, sched=s, workspace=ws, stream=stream,
+                                                   nnz=nnz)))
         for name, fn in ops:
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -114,7 +120,7 @@ def main(argv=None):
             print("| %s | %d | %.3f | %.0f | %.0f | %.0f %% | %.3f | %.2fx | %.1f | %s |"
                   % (name, F, t, 2.0 * nnz * F / t / 1e6, bg / t / 1e6, 100 * bg / t / 1e6 / HBM_PEAK_GBS, tb, tb / t, cold,
                      short(choice)), flush=True)
-        if args.vendor:
+        if args.vendor and args.dtype == "f32":
             try:
                 Asp = torch.sparse_csr_tensor(rp.to(torch.int64), ci.to(torch.int64), va, size=(N, M))
                 tv = timed(lambda: torch.sparse.mm(Asp, B), 3)

@@ -179,3 +179,28 @@ def test_config4_large_sparse_full_size(torch, ab, handle):
     check_spmm(torch, ab, handle, A, d_csr, 100, rows, seed=100)
     check_sddmm(torch, ab, handle, A, d_csr, 16, rows, seed=16)
     check_sddmm(torch, ab, handle, A, d_csr, 128, rows, seed=128)
+    # bf16 dense operands with fp32 accumulation (the paper's mixed-precision extension), F = 128
+    rng = np.random.default_rng(7)
+    F = 128
+    Bb = W.float_to_bf16_bits(rng.standard_normal((A.n_cols, F), dtype=np.float32)).reshape(A.n_cols, F)
+    Xb = W.float_to_bf16_bits(rng.standard_normal((A.n_rows, F), dtype=np.float32)).reshape(A.n_rows, F)
+    dB, dX = dev(Bb, torch), dev(Xb, torch)
+    C = torch.full((A.n_rows, F), float("nan"), dtype=torch.float32, device="cuda")
+    out = torch.full((A.nnz,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(handle.workspace_bytes(ab.OP_SPMM, A.n_rows, A.nnz, F), dtype=torch.uint8, device="cuda")
+    handle.spmm(A.n_rows, A.n_cols, *d_csr, dB, C, F, dt=ab.BF16, workspace=ws)
+    handle.sddmm(A.n_rows, A.n_cols, d_csr[0], d_csr[1], dX, dB, out, F, dt=ab.BF16, workspace=ws)
+    torch.cuda.synchronize()
+    As = W.row_slice(A, rows)
+    absb = lambda x: x & np.uint16(0x7FFF)
+    ref = oracle.spmm(As.rowptr, As.colind, As.val, Bb)
+    ref_abs = oracle.spmm(As.rowptr, As.colind, np.abs(As.val), absb(Bb))
+    got = C[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert rel_l1_rows(got, ref, ref_abs).max() <= 2e-2
+    rp = A.rowptr.astype(np.int64)
+    idx = np.concatenate([np.arange(rp[r], rp[r + 1]) for r in rows])
+    Xs = np.ascontiguousarray(Xb[rows])
+    ref = oracle.sddmm(As.rowptr, As.colind, Xs, Bb)
+    ref_abs = oracle.sddmm(As.rowptr, As.colind, absb(Xs), absb(Bb))
+    got = out[torch.from_numpy(idx).cuda()].cpu().numpy()
+    assert rel_l1_segments(got, ref, As.rowptr, ref_abs).max() <= 2e-2
