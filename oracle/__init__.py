@@ -164,3 +164,34 @@ def decide(t_cand, t_baseline: float, alpha: float) -> int:
     lib = _load()
     t = np.ascontiguousarray(t_cand, dtype=np.float64)
     return int(lib.oracle_decide(ctypes.c_int32(t.shape[0]), _p(t), ctypes.c_double(t_baseline), ctypes.c_double(alpha)))
+
+
+def csr_transpose(rowptr, colind, val, n_cols: int):
+    """A^T as CSR: returns (t_rowptr, t_colind, t_val, perm); stable (source rows ascending inside a row of A^T)."""
+    lib = _load()
+    rowptr, colind = _i32(rowptr), _i32(colind)
+    val = np.ascontiguousarray(val, dtype=np.float32)
+    n_rows, nnz = rowptr.shape[0] - 1, int(rowptr[-1])
+    t_rowptr = np.zeros(n_cols + 1, dtype=np.int32)
+    t_colind = np.zeros(max(nnz, 1), dtype=np.int32)
+    t_val = np.zeros(max(nnz, 1), dtype=np.float32)
+    perm = np.zeros(max(nnz, 1), dtype=np.int32)
+    rc = lib.oracle_csr_transpose(ctypes.c_int64(n_rows), ctypes.c_int64(n_cols), _p(rowptr), _p(colind), _p(val),
+                                  _p(t_rowptr), _p(t_colind), _p(t_val), _p(perm))
+    assert rc == 0
+    return t_rowptr, t_colind[:nnz], t_val[:nnz], perm[:nnz]
+
+
+def row_softmax_backward(rowptr, P, dP) -> np.ndarray:
+    """dS = P * (dP - rowsum(P * dP)) over the stored entries of each row (and head); float64."""
+    lib = _load()
+    rowptr = _i32(rowptr)
+    P = np.ascontiguousarray(P, dtype=np.float64)
+    dP = np.ascontiguousarray(dP, dtype=np.float64)
+    assert P.shape == dP.shape
+    H = 1 if P.ndim == 1 else P.shape[1]
+    dS = np.zeros_like(P)
+    rc = lib.oracle_row_softmax_backward(ctypes.c_int64(rowptr.shape[0] - 1), _p(rowptr), _p(P), _p(dP), ctypes.c_int32(H),
+                                         _p(dS))
+    assert rc == 0
+    return dS

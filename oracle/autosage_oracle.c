@@ -20,6 +20,10 @@
  *   oracle_hub_partition Kernel-variant table: heavy rows (degree >= hubT) vs others;
  *                        the chunking of heavy rows is this project's own scheme.
  *   oracle_decide        Scheduler subsection + decision sketch + Proposition 1.
+ *   oracle_csr_transpose, oracle_row_softmax_backward
+ *                        the adjoints needed when the operators sit in a training step (Introduction:
+ *                        training throughput is bounded by these aggregations): d/dB of C = A B is A^T dC,
+ *                        and the Jacobian-transpose product of the row-softmax.
  *
  * All pins for these functions live in tests/test_oracle_*.py.
  */
@@ -247,4 +251,47 @@ int oracle_decide(int32_t n_cand, const double* t_cand, double t_baseline, doubl
         }
     }
     return (tstar <= alpha * t_baseline) ? best : -1;
+}
+
+/* A^T as CSR (n_cols rows).  Stable: inside a row of A^T the entries keep the order of their source
+ * rows (ascending row index, and storage order for duplicates).  perm[q] = position in A of entry q
+ * of A^T, so t_val[q] = val[perm[q]] and t_colind[q] = row of A that owns perm[q].
+ * val / t_val may be NULL. */
+int oracle_csr_transpose(int64_t n_rows, int64_t n_cols, const int32_t* rowptr, const int32_t* colind,
+                         const float* val, int32_t* t_rowptr, int32_t* t_colind, float* t_val, int32_t* perm)
+{
+    int64_t nnz = rowptr[n_rows];
+    int32_t* next = (int32_t*)calloc((size_t)n_cols + 1, sizeof(int32_t));
+    if (!next) return 1;
+    for (int64_t c = 0; c <= n_cols; ++c) t_rowptr[c] = 0;
+    for (int64_t p = 0; p < nnz; ++p) t_rowptr[colind[p] + 1] += 1;
+    for (int64_t c = 0; c < n_cols; ++c) t_rowptr[c + 1] += t_rowptr[c];
+    for (int64_t c = 0; c < n_cols; ++c) next[c] = t_rowptr[c];
+    for (int64_t i = 0; i < n_rows; ++i) {
+        for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+            int32_t q = next[colind[p]]++;
+            t_colind[q] = (int32_t)i;
+            if (val && t_val) t_val[q] = val[p];
+            perm[q] = (int32_t)p;
+        }
+    }
+    free(next);
+    return 0;
+}
+
+/* Jacobian-transpose product of the row-softmax: for every row and head,
+ * dS[p,h] = P[p,h] * (dP[p,h] - sum_q P[q,h] * dP[q,h]), q over the stored entries of the row. */
+int oracle_row_softmax_backward(int64_t n_rows, const int32_t* rowptr, const double* P, const double* dP, int32_t H,
+                                double* dS)
+{
+    int64_t i;
+#pragma omp parallel for schedule(dynamic, 256)
+    for (i = 0; i < n_rows; ++i) {
+        for (int32_t h = 0; h < H; ++h) {
+            double dot = 0.0;
+            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) dot += P[p * H + h] * dP[p * H + h];
+            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) dS[p * H + h] = P[p * H + h] * (dP[p * H + h] - dot);
+        }
+    }
+    return 0;
 }

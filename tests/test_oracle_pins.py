@@ -358,3 +358,54 @@ def test_decide_never_regresses_for_alpha_at_most_one():
             assert t[c] == t.min() and t[c] <= alpha * tb
         else:
             assert k == 0 or t.min() > alpha * tb
+
+
+# ------------------------------------------------------------- adjoints ---
+def test_transpose_matches_library_transpose_and_is_stable():
+    A, rng = tiny_csr(37, 23, 4.0, seed=41)
+    t_rowptr, t_colind, t_val, perm = oracle.csr_transpose(A.rowptr, A.colind, A.val, A.n_cols)
+    M = sp.csr_matrix((A.val, A.colind, A.rowptr), shape=(37, 23))
+    T = M.T.tocsr()
+    T.sort_indices()
+    assert np.array_equal(t_rowptr, T.indptr) and np.array_equal(t_colind, T.indices) and np.array_equal(t_val, T.data)
+    assert np.array_equal(t_val, A.val[perm])
+    rows = np.repeat(np.arange(37), A.degrees)
+    assert np.array_equal(t_colind, rows[perm])
+    # dense check of the use it is for: d/dB of C = A B is A^T dC
+    dC = rng.standard_normal((37, 5)).astype(np.float32)
+    dB = oracle.spmm(t_rowptr, t_colind, t_val, dC)
+    np.testing.assert_allclose(dB, densify(A).T @ dC.astype(np.float64), rtol=1e-13, atol=1e-13)
+    # hand-worked: rows {0: cols 2,0 (unsorted)}, {1: col 2}, {2: cols 2,2 (duplicate)}
+    rp = np.array([0, 2, 3, 5], np.int32)
+    ci = np.array([2, 0, 2, 2, 2], np.int32)
+    va = np.array([1, 2, 3, 4, 5], np.float32)
+    t_rowptr, t_colind, t_val, perm = oracle.csr_transpose(rp, ci, va, 3)
+    assert t_rowptr.tolist() == [0, 1, 1, 5] and t_colind.tolist() == [0, 0, 1, 2, 2]
+    assert t_val.tolist() == [2, 1, 3, 4, 5] and perm.tolist() == [1, 0, 2, 3, 4]
+
+
+def test_softmax_backward_matches_autograd_and_finite_differences():
+    torch = pytest.importorskip("torch")
+    A, rng = tiny_csr(15, 15, 4.0, seed=43)
+    H = 3
+    s = rng.standard_normal((A.nnz, H))
+    dP = rng.standard_normal((A.nnz, H))
+    P = oracle.row_softmax(A.rowptr, s)
+    dS = oracle.row_softmax_backward(A.rowptr, P, dP)
+    for i in range(A.n_rows):
+        p0, p1 = A.rowptr[i], A.rowptr[i + 1]
+        if p1 == p0:
+            continue
+        x = torch.tensor(s[p0:p1], dtype=torch.float64, requires_grad=True)
+        torch.softmax(x, dim=0).backward(torch.tensor(dP[p0:p1]))
+        np.testing.assert_allclose(dS[p0:p1], x.grad.numpy(), rtol=1e-11, atol=1e-13)
+    # central finite difference of sum(dP * softmax(s)) in one coordinate
+    p, h, eps = int(A.rowptr[3]), 1, 1e-6
+    sp_, sm_ = s.copy(), s.copy()
+    sp_[p, h] += eps
+    sm_[p, h] -= eps
+    fd = ((oracle.row_softmax(A.rowptr, sp_) - oracle.row_softmax(A.rowptr, sm_)) * dP).sum() / (2 * eps)
+    assert abs(fd - dS[p, h]) <= 1e-8
+    # each row's gradient sums to zero (softmax is shift invariant)
+    sums = np.add.reduceat(dS, A.rowptr[:-1][A.degrees > 0], axis=0)
+    np.testing.assert_allclose(sums, 0.0, atol=1e-14)
