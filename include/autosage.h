@@ -242,6 +242,38 @@ autosage_status_t autosage_cache_lookup(autosage_handle_t h, uint64_t graph_sig,
 autosage_status_t autosage_cache_insert(autosage_handle_t h, uint64_t graph_sig, int32_t F, int32_t H,
                                         autosage_op_t op, autosage_dtype_t dt, const autosage_schedule_t* sched);
 
+/* ---- adjoints for training steps ---------------------------------------------------------
+ * The paper motivates the operators by training throughput (Introduction) and leaves end-to-end
+ * training to future work; these entry points supply what a backward pass needs beyond the forward
+ * operators themselves: d/dB (C = A B) = A^T dC needs A^T; d/dval = SDDMM(dC, B) is autosage_sddmm;
+ * the row-softmax has its own Jacobian-transpose product. */
+
+/* dS[p,h] = P[p,h] * (dP[p,h] - sum_q P[q,h] dP[q,h]) over the stored entries q of the row of p.
+ * P, dP, dS are [nnz, H] fp32 dev arrays; dS may alias dP.  hub_t / hub_chunk / workspace as in
+ * autosage_csr_row_softmax (autosage_workspace_bytes(AUTOSAGE_OP_SOFTMAX, ...) is enough). */
+autosage_status_t autosage_csr_row_softmax_backward(autosage_handle_t h, int64_t n_rows, int64_t nnz,
+                                                    const int32_t* rowptr, const float* P, const float* dP,
+                                                    float* dS, int32_t H, int32_t hub_t, int32_t hub_chunk,
+                                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* A^T as CSR.  t_rowptr[n_cols+1], t_colind[nnz] (dev) describe the n_cols x n_rows matrix A^T; inside a
+ * row of A^T the entries are in ascending source-row order (storage order for duplicates), so the result
+ * is unique.  perm[nnz] (dev, may be NULL) receives the position in A of every entry of A^T; t_val[nnz]
+ * (dev) = val[perm] (both NULL for a pattern-only transpose).  Integer outputs are bit-reproducible.
+ * The workspace size comes from autosage_csr_transpose_workspace_bytes (needs a device handle: the
+ * sort primitive sizes its scratch for the device).  Enqueues only; no synchronisation. */
+autosage_status_t autosage_csr_transpose_workspace_bytes(autosage_handle_t h, int64_t n_rows, int64_t n_cols,
+                                                         int64_t nnz, size_t* bytes);
+autosage_status_t autosage_csr_transpose(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                         const int32_t* rowptr, const int32_t* colind, const float* val,
+                                         int32_t* t_rowptr, int32_t* t_colind, float* t_val, int32_t* perm,
+                                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* out[q, 0..width) = in[perm[q], 0..width) for q < n (fp32, dev): carries per-nonzero values (for
+ * instance attention probabilities [nnz, H]) into the order of a transposed pattern.  in != out. */
+autosage_status_t autosage_gather_values(autosage_handle_t h, int64_t n, int32_t width, const int32_t* perm,
+                                         const float* in, float* out, void* stream);
+
 /* Telemetry (Contributions: deployment toggles and telemetry).  Between profile_begin and
  * profile_read every kernel stage the handle launches is bracketed by a pair of HIP events on its
  * stream.  profile_read waits for the recorded stages, writes JSON {"stage":{"calls":n,"total_ms":t},...}

@@ -72,6 +72,10 @@ def _load():
         "autosage_cache_insert": [vp, c.c_uint64, i32, i32, c.c_int, c.c_int, sp],
         "autosage_decide_attention": [vp, i64, i64, vp, vp, vp, vp, vp, vp, i32, i32, c.c_float, c.c_int, vp, sz, vp, sp],
         "autosage_baseline_schedule": [sp],
+        "autosage_csr_row_softmax_backward": [vp, i64, i64, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp],
+        "autosage_csr_transpose_workspace_bytes": [vp, i64, i64, i64, c.POINTER(sz)],
+        "autosage_csr_transpose": [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
+        "autosage_gather_values": [vp, i64, i32, vp, vp, vp, vp],
         "autosage_profile_begin": [vp],
         "autosage_profile_read": [vp, c.c_char_p, sz],
     }
@@ -193,6 +197,31 @@ class Handle:
         _check(_lib.autosage_csr_attention(self._h, N, nnz, _ptr(rowptr), _ptr(colind), None, _ptr(Q), _ptr(K), _ptr(V),
                                            _ptr(O), H, d, float(scale), in_dt, _sched(sched), _ptr(workspace), ws_bytes,
                                            _stream(stream)), "autosage_csr_attention")
+
+    # -- adjoint helpers --------------------------------------------------------------
+    def csr_row_softmax_backward(self, n_rows, nnz, rowptr, P, dP, dS, H=1, hub_t=0, hub_chunk=0, workspace=None,
+                                 stream=None):
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        _check(_lib.autosage_csr_row_softmax_backward(self._h, n_rows, nnz, _ptr(rowptr), _ptr(P), _ptr(dP), _ptr(dS), H,
+                                                      hub_t, hub_chunk, _ptr(workspace), ws_bytes, _stream(stream)),
+               "autosage_csr_row_softmax_backward")
+
+    def csr_transpose_workspace_bytes(self, n_rows, n_cols, nnz) -> int:
+        out = ctypes.c_size_t()
+        _check(_lib.autosage_csr_transpose_workspace_bytes(self._h, n_rows, n_cols, nnz, ctypes.byref(out)),
+               "autosage_csr_transpose_workspace_bytes")
+        return int(out.value)
+
+    def csr_transpose(self, n_rows, n_cols, nnz, rowptr, colind, val, t_rowptr, t_colind, t_val, perm, workspace,
+                      stream=None):
+        ws_bytes = workspace.numel() * workspace.element_size()
+        _check(_lib.autosage_csr_transpose(self._h, n_rows, n_cols, nnz, _ptr(rowptr), _ptr(colind), _ptr(val),
+                                           _ptr(t_rowptr), _ptr(t_colind), _ptr(t_val), _ptr(perm), _ptr(workspace),
+                                           ws_bytes, _stream(stream)), "autosage_csr_transpose")
+
+    def gather_values(self, n, width, perm, src, dst, stream=None):
+        _check(_lib.autosage_gather_values(self._h, n, width, _ptr(perm), _ptr(src), _ptr(dst), _stream(stream)),
+               "autosage_gather_values")
 
     # -- metadata ----------------------------------------------------------------------
     def hub_partition(self, n_rows, rowptr, hub_t, hub_chunk, hub_rows, chunk_ptr, light_rows, workspace, stream=None):

@@ -893,3 +893,92 @@ extern "C" autosage_status_t autosage_profile_read(autosage_handle_t h, char* js
     json_buf[m] = '\0';
     return AUTOSAGE_OK;
 }
+
+// ------------------------------------------------------------------------------------------
+// adjoint helpers (training steps): row-softmax backward, CSR transpose, value gather
+// ------------------------------------------------------------------------------------------
+extern "C" autosage_status_t autosage_csr_row_softmax_backward(autosage_handle_t h, int64_t n_rows, int64_t nnz,
+                                                               const int32_t* rowptr, const float* P, const float* dP,
+                                                               float* dS, int32_t H, int32_t hub_t, int32_t hub_chunk,
+                                                               void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!h || !sizes_ok(n_rows, 0, nnz) || H <= 0 || hub_t < 0 || hub_chunk < 0) return AUTOSAGE_ERR_INVALID_ARG;
+    if (hub_t > 0 && hub_t < kMinHubT) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (n_rows == 0 || nnz == 0) return AUTOSAGE_OK;
+    if (!rowptr || !P || !dP || !dS) return AUTOSAGE_ERR_INVALID_ARG;
+    const int chunk = hub_t > 0 ? (hub_chunk > 0 ? hub_chunk : hub_t) : 0;
+    if (hub_t > 0 && chunk < kMinHubT) return AUTOSAGE_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SoftmaxBwdArgs a{};
+    a.rows = RowMap{0, 1, (int32_t)n_rows, 0};
+    a.rowptr = rowptr;
+    a.P = P;
+    a.dP = dP;
+    a.dS = dS;
+    a.H = H;
+    HubMeta meta{};
+    float* part = nullptr;
+    if (hub_t > 0) {
+        if (!carve_hub(workspace, workspace_bytes, n_rows, nnz, hub_t, chunk, H, &meta, &part, nullptr))
+            return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+        STAGE(h, "hub_partition", st, launch_hub_partition(a.rows, rowptr, hub_t, chunk, meta, st));
+    }
+    STAGE(h, "softmax_bwd", st, launch_softmax_bwd(a, hub_t, chunk, hub_t > 0 ? &meta : nullptr, part, st));
+    return AUTOSAGE_OK;
+}
+
+static size_t transpose_workspace(int64_t nnz, int64_t n_cols, size_t* temp_bytes)
+{
+    const size_t ints = align_up(sizeof(int32_t) * (size_t)(nnz > 0 ? nnz : 1), 256);
+    const size_t temp = align_up(transpose_sort_temp_bytes(nnz > 0 ? nnz : 1, n_cols), 256);
+    if (temp_bytes) *temp_bytes = temp;
+    return 3 * ints + temp;                 // sorted keys, iota, permutation (when the caller keeps none), sort scratch
+}
+
+extern "C" autosage_status_t autosage_csr_transpose_workspace_bytes(autosage_handle_t h, int64_t n_rows, int64_t n_cols,
+                                                                    int64_t nnz, size_t* bytes)
+{
+    if (!h || !bytes || !sizes_ok(n_rows, n_cols, nnz)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;          // the sort primitive sizes its scratch for the device
+    *bytes = transpose_workspace(nnz, n_cols, nullptr);
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_csr_transpose(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                                    const int32_t* rowptr, const int32_t* colind, const float* val,
+                                                    int32_t* t_rowptr, int32_t* t_colind, float* t_val, int32_t* perm,
+                                                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!h || !sizes_ok(n_rows, n_cols, nnz) || !rowptr || !t_rowptr) return AUTOSAGE_ERR_INVALID_ARG;
+    if (nnz > 0 && (!colind || !t_colind)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (nnz > 0 && (val == nullptr) != (t_val == nullptr)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    size_t temp_bytes = 0;
+    const size_t need = transpose_workspace(nnz, n_cols, &temp_bytes);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uint64_t>(workspace) & 255u) != 0)
+        return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+    const size_t ints = align_up(sizeof(int32_t) * (size_t)(nnz > 0 ? nnz : 1), 256);
+    char* p = static_cast<char*>(workspace);
+    int32_t* keys_out = reinterpret_cast<int32_t*>(p);
+    int32_t* iota = reinterpret_cast<int32_t*>(p + ints);
+    int32_t* perm_buf = perm ? perm : reinterpret_cast<int32_t*>(p + 2 * ints);
+    void* temp = p + 3 * ints;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    STAGE(h, "csr_transpose", st,
+          launch_csr_transpose(n_rows, n_cols, nnz, rowptr, colind, val, t_rowptr, t_colind, t_val, perm_buf, keys_out, iota,
+                               temp, temp_bytes, st));
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_gather_values(autosage_handle_t h, int64_t n, int32_t width, const int32_t* perm,
+                                                    const float* in, float* out, void* stream)
+{
+    if (!h || n < 0 || width <= 0 || n >= (int64_t(1) << 31)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (n == 0) return AUTOSAGE_OK;
+    if (!perm || !in || !out || in == out) return AUTOSAGE_ERR_INVALID_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    STAGE(h, "gather_values", st, launch_gather_rows(perm, n, width, in, out, st));
+    return AUTOSAGE_OK;
+}

@@ -130,6 +130,27 @@ size_t attn_fused_part_floats(const AttnShape& s);
 hipError_t launch_attn_fused_rows(const AttnArgs& a, const AttnShape& s, hipStream_t stream);
 hipError_t launch_attn_fused_hub(const AttnArgs& a, const AttnShape& s, const HubMeta& meta, float* part, hipStream_t stream);
 
+struct SoftmaxBwdArgs {
+    RowMap rows;
+    const int32_t* rowptr;
+    const float* P;        // [nnz, H] softmax output
+    const float* dP;       // [nnz, H] gradient with respect to P (may alias dS)
+    float* dS;             // [nnz, H] gradient with respect to the scores
+    int32_t H;
+};
+
+// dS = P * (dP - rowsum(P * dP)); hub rows (degree >= hub_t) through per-chunk partial dots in `part` ([cap_chunks, H]).
+hipError_t launch_softmax_bwd(const SoftmaxBwdArgs& a, int32_t hub_t, int32_t hub_chunk, const HubMeta* meta, float* part,
+                              hipStream_t stream);
+
+// CSR transpose: stable sort of the nonzeros by column + index kernels.
+size_t transpose_sort_temp_bytes(int64_t nnz, int64_t n_cols);
+hipError_t launch_csr_transpose(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
+                                const float* val, int32_t* t_rowptr, int32_t* t_colind, float* t_val, int32_t* perm,
+                                int32_t* keys_out, int32_t* iota, void* temp, size_t temp_bytes, hipStream_t stream);
+// out[q, :] = in[perm[q], :] for rows of `width` floats.
+hipError_t launch_gather_rows(const int32_t* perm, int64_t n, int32_t width, const float* in, float* out, hipStream_t stream);
+
 // Heavy/light partition of the rows of `rows` (index metadata, integer only).
 hipError_t launch_hub_partition(const RowMap& rows, const int32_t* rowptr, int32_t hub_t, int32_t hub_chunk,
                                 const HubMeta& meta, hipStream_t stream);

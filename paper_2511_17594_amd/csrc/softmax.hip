@@ -228,6 +228,127 @@ __global__ void __launch_bounds__(1024) softmax_hub_normalise_kernel(SoftmaxDev 
     }
 }
 
+// ---- backward: dS = P * (dP - sum_q P_q dP_q) per row and head ------------------------------------
+struct SoftmaxBwdDev {
+    RowMap rows;
+    const int32_t* __restrict__ rowptr;
+    const float* P;
+    const float* dP;        // may alias dS
+    float* dS;
+    int32_t H;
+    int32_t hp_shift;
+    int32_t hub_t;
+    int32_t hub_chunk;
+    const HubCounts* __restrict__ counts;
+    const int32_t* __restrict__ hub_rows;
+    const int32_t* __restrict__ chunk_ptr;
+    float* part;            // [cap_chunks, H] partial dots
+};
+
+__global__ void __launch_bounds__(1024) softmax_bwd_rows_kernel(SoftmaxBwdDev a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int idx = wave_uniform(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
+    if (idx >= a.rows.count) return;
+    const int row = row_of(a.rows, idx);
+    const int p0 = wave_uniform(a.rowptr[row]);
+    const int p1 = wave_uniform(a.rowptr[row + 1]);
+    const int deg = p1 - p0;
+    if (deg <= 0) return;
+    if (a.hub_t > 0 && deg >= a.hub_t) return;
+    const int HP = 1 << a.hp_shift;
+    const int PL = kWave >> a.hp_shift;
+    const int hh = lane & (HP - 1);
+    const int pl = lane >> a.hp_shift;
+    for (int hp = 0; hp < a.H; hp += HP) {
+        const int h = hp + hh;
+        const bool hv = h < a.H;
+        float dot = 0.f;
+        if (hv) {
+            for (int p = p0 + pl; p < p1; p += PL) {
+                const int64_t e = (int64_t)p * a.H + h;
+                dot = fmaf(a.P[e], a.dP[e], dot);
+            }
+        }
+        for (int off = HP; off < kWave; off <<= 1) dot += __shfl_xor(dot, off, kWave);
+        if (hv) {
+            for (int p = p0 + pl; p < p1; p += PL) {
+                const int64_t e = (int64_t)p * a.H + h;
+                a.dS[e] = a.P[e] * (a.dP[e] - dot);
+            }
+        }
+    }
+}
+
+__global__ void __launch_bounds__(1024) softmax_bwd_hub_partial_kernel(SoftmaxBwdDev a)
+{
+    __shared__ float lds[16 * kWave];
+    const int chunk = blockIdx.x;
+    if (chunk >= a.counts->n_chunks) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int wpg = blockDim.x >> 6;
+    const int k_hub = softmax_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
+    const int row = row_of(a.rows, a.hub_rows[k_hub]);
+    const int t = chunk - a.chunk_ptr[k_hub];
+    const int q0 = a.rowptr[row] + t * a.hub_chunk;
+    const int q1 = min(q0 + a.hub_chunk, a.rowptr[row + 1]);
+    const int HP = 1 << a.hp_shift;
+    const int PL = kWave >> a.hp_shift;
+    const int hh = lane & (HP - 1);
+    const int pl = lane >> a.hp_shift;
+    for (int hp = 0; hp < a.H; hp += HP) {
+        const int h = hp + hh;
+        const bool hv = h < a.H;
+        float dot = 0.f;
+        if (hv) {
+            for (int p = q0 + wave * PL + pl; p < q1; p += wpg * PL) {
+                const int64_t e = (int64_t)p * a.H + h;
+                dot = fmaf(a.P[e], a.dP[e], dot);
+            }
+        }
+        for (int off = HP; off < kWave; off <<= 1) dot += __shfl_xor(dot, off, kWave);
+        if (pl == 0) lds[wave * kWave + hh] = dot;
+        __syncthreads();
+        if (wave == 0 && pl == 0 && hv) {
+            float tot = lds[hh];
+            for (int w = 1; w < wpg; ++w) tot += lds[w * kWave + hh];       // fixed wavefront order
+            a.part[(int64_t)chunk * a.H + h] = tot;
+        }
+        __syncthreads();
+    }
+}
+
+__global__ void __launch_bounds__(1024) softmax_bwd_hub_apply_kernel(SoftmaxBwdDev a)
+{
+    const int chunk = blockIdx.x;
+    if (chunk >= a.counts->n_chunks) return;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int wpg = blockDim.x >> 6;
+    const int k_hub = softmax_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
+    const int row = row_of(a.rows, a.hub_rows[k_hub]);
+    const int c0 = a.chunk_ptr[k_hub];
+    const int c1 = a.chunk_ptr[k_hub + 1];
+    const int t = chunk - c0;
+    const int q0 = a.rowptr[row] + t * a.hub_chunk;
+    const int q1 = min(q0 + a.hub_chunk, a.rowptr[row + 1]);
+    const int HP = 1 << a.hp_shift;
+    const int PL = kWave >> a.hp_shift;
+    const int hh = lane & (HP - 1);
+    const int pl = lane >> a.hp_shift;
+    for (int hp = 0; hp < a.H; hp += HP) {
+        const int h = hp + hh;
+        if (h >= a.H) continue;
+        float dot = 0.f;
+        for (int c = c0; c < c1; ++c) dot += a.part[(int64_t)c * a.H + h];   // ascending chunk order
+        for (int p = q0 + wave * PL + pl; p < q1; p += wpg * PL) {
+            const int64_t e = (int64_t)p * a.H + h;
+            a.dS[e] = a.P[e] * (a.dP[e] - dot);
+        }
+    }
+}
+
 inline int log2_ceil_pow2(int x)
 {
     int s = 0;
@@ -272,6 +393,35 @@ hipError_t launch_softmax_hub(const SoftmaxArgs& a, int32_t hub_chunk, const Hub
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(softmax_hub_normalise_kernel, dim3(meta.cap_chunks), dim3(256), 0, stream, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax_bwd(const SoftmaxBwdArgs& a, int32_t hub_t, int32_t hub_chunk, const HubMeta* meta, float* part,
+                              hipStream_t stream)
+{
+    SoftmaxBwdDev d{};
+    d.rows = a.rows;
+    d.rowptr = a.rowptr;
+    d.P = a.P;
+    d.dP = a.dP;
+    d.dS = a.dS;
+    d.H = a.H;
+    d.hp_shift = log2_ceil_pow2(a.H < kWave ? a.H : kWave);
+    d.hub_t = hub_t;
+    d.hub_chunk = hub_chunk;
+    const int n_blocks = (a.rows.count + 3) / 4;
+    if (n_blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(softmax_bwd_rows_kernel, dim3(n_blocks), dim3(4 * kWave), 0, stream, d);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || hub_t <= 0 || !meta || meta->cap_chunks == 0 || meta->cap_hub == 0) return e;
+    d.counts = meta->counts;
+    d.hub_rows = meta->hub_rows;
+    d.chunk_ptr = meta->chunk_ptr;
+    d.part = part;
+    hipLaunchKernelGGL(softmax_bwd_hub_partial_kernel, dim3(meta->cap_chunks), dim3(256), 0, stream, d);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(softmax_bwd_hub_apply_kernel, dim3(meta->cap_chunks), dim3(256), 0, stream, d);
     return hipGetLastError();
 }
 

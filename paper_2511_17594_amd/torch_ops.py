@@ -1,0 +1,286 @@
+"""PyTorch operators over the C-ABI library (the paper's Implementation section exposes
+`autosage::spmm_csr`, `autosage::spmm_csr_split` and `autosage::sddmm_csr`, and its CSR-attention
+subsection adds `sddmm_csr_auto` and `csr_attention_forward`).
+
+Importing this module registers, in the `autosage` namespace of `torch.ops`:
+
+    spmm_csr(rowptr, colind, val, B) -> C                    selector-chosen schedule
+    spmm_csr_split(rowptr, colind, val, B, hub_t) -> C       wavefront-per-row + hub split at hub_t
+    sddmm_csr(rowptr, colind, X, Y) -> out                   selector-chosen schedule ("sddmm_csr_auto")
+    csr_row_softmax(rowptr, s) -> P                          s is [nnz] or [nnz, H]
+    csr_attention_forward(rowptr, colind, Q, K, V, scale) -> O
+
+Every arithmetic step runs in the library's HIP kernels; this file only allocates outputs and
+workspaces with torch, passes pointers, and wires the adjoints (themselves library calls: SpMM on
+the transposed pattern, SDDMM, the row-softmax backward) into autograd.  Index tensors are int32 on
+the GPU; dense tensors are float32 (bfloat16 is accepted as an input dtype of the forward kernels).
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional, Tuple
+
+import torch
+
+from . import binding as ab
+
+_handles: Dict[int, ab.Handle] = {}
+_transposes: Dict[Tuple, Tuple] = {}
+
+
+def handle(device: Optional[torch.device] = None) -> ab.Handle:
+    """The per-device library handle used by the operators (created on first use)."""
+    idx = torch.cuda.current_device() if device is None or device.index is None else device.index
+    if idx not in _handles:
+        _handles[idx] = ab.Handle(idx)
+    return _handles[idx]
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return ab.F32
+    if t.dtype == torch.bfloat16:
+        return ab.BF16
+    raise TypeError("dense operands must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _check_csr(rowptr, colind):
+    if rowptr.dtype != torch.int32 or colind.dtype != torch.int32 or not rowptr.is_cuda or not colind.is_cuda:
+        raise TypeError("rowptr and colind must be int32 CUDA tensors")
+
+
+def _spmm(rowptr, colind, val, B, sched, n_rows=None, ldb=None, out=None, ldc=None, F=None):
+    _check_csr(rowptr, colind)
+    h = handle(B.device)
+    n_rows = rowptr.numel() - 1 if n_rows is None else n_rows
+    n_cols = B.shape[0]
+    F = B.shape[1] if F is None else F
+    nnz = colind.numel()
+    C = torch.empty((n_rows, F), dtype=torch.float32, device=B.device) if out is None else out
+    ws = _ws(h.workspace_bytes(ab.OP_SPMM, n_rows, nnz, F, 1, sched), B.device)
+    h.spmm(n_rows, n_cols, rowptr, colind, val, B, C, F, dt=_dt(B), sched=sched, workspace=ws, nnz=nnz, ldb=ldb, ldc=ldc)
+    return C
+
+
+def _sddmm(rowptr, colind, X, Y, sched=None, ldx=None, ldy=None, F=None, out=None):
+    _check_csr(rowptr, colind)
+    h = handle(X.device)
+    n_rows, n_cols = rowptr.numel() - 1, Y.shape[0]
+    F = X.shape[1] if F is None else F
+    nnz = colind.numel()
+    out = torch.empty(nnz, dtype=torch.float32, device=X.device) if out is None else out
+    ws = _ws(h.workspace_bytes(ab.OP_SDDMM, n_rows, nnz, F, 1, sched), X.device)
+    h.sddmm(n_rows, n_cols, rowptr, colind, X, Y, out, F, dt=_dt(X), sched=sched, workspace=ws, nnz=nnz, ldx=ldx, ldy=ldy)
+    return out
+
+
+def transpose(rowptr: torch.Tensor, colind: torch.Tensor, n_cols: int):
+    """(t_rowptr, t_colind, perm) of the pattern, cached per (storage, version) of the index tensors."""
+    key = (rowptr.data_ptr(), colind.data_ptr(), rowptr._version, colind._version, colind.numel(), n_cols)
+    hit = _transposes.get(key)
+    if hit is not None:
+        return hit
+    h = handle(rowptr.device)
+    n_rows, nnz = rowptr.numel() - 1, colind.numel()
+    t_rowptr = torch.empty(n_cols + 1, dtype=torch.int32, device=rowptr.device)
+    t_colind = torch.empty(max(nnz, 1), dtype=torch.int32, device=rowptr.device)
+    perm = torch.empty(max(nnz, 1), dtype=torch.int32, device=rowptr.device)
+    ws = _ws(h.csr_transpose_workspace_bytes(n_rows, n_cols, nnz), rowptr.device)
+    h.csr_transpose(n_rows, n_cols, nnz, rowptr, colind, None, t_rowptr, t_colind, None, perm, ws)
+    if len(_transposes) >= 8:
+        _transposes.pop(next(iter(_transposes)))
+    _transposes[key] = (t_rowptr, t_colind[:nnz], perm[:nnz])
+    return _transposes[key]
+
+
+def _gather(perm, values):
+    """values[perm] through the library (values is [nnz] or [nnz, w] float32)."""
+    out = torch.empty_like(values)
+    w = 1 if values.dim() == 1 else values.shape[1]
+    handle(values.device).gather_values(perm.numel(), w, perm, values.contiguous(), out)
+    return out
+
+
+# ----------------------------------------------------------------------------- SpMM ---
+@torch.library.custom_op("autosage::spmm_csr", mutates_args=())
+def spmm_csr(rowptr: torch.Tensor, colind: torch.Tensor, val: torch.Tensor, B: torch.Tensor) -> torch.Tensor:
+    return _spmm(rowptr, colind, val, B.contiguous(), None)
+
+
+@torch.library.custom_op("autosage::spmm_csr_split", mutates_args=())
+def spmm_csr_split(rowptr: torch.Tensor, colind: torch.Tensor, val: torch.Tensor, B: torch.Tensor, hub_t: int) -> torch.Tensor:
+    sched = ab.Schedule(mapping=ab.MAP_WAVE_ROW, hub_t=hub_t, hub_chunk=hub_t)
+    return _spmm(rowptr, colind, val, B.contiguous(), sched)
+
+
+def _spmm_fake(rowptr, colind, val, B, *_):
+    return B.new_empty((rowptr.shape[0] - 1, B.shape[1]), dtype=torch.float32)
+
+
+spmm_csr.register_fake(_spmm_fake)
+spmm_csr_split.register_fake(_spmm_fake)
+
+
+def _spmm_setup(ctx, inputs, output):
+    rowptr, colind, val, B = inputs[:4]
+    ctx.save_for_backward(rowptr, colind, val, B)
+
+
+def _spmm_backward(ctx, dC):
+    rowptr, colind, val, B = ctx.saved_tensors
+    dC = dC.contiguous()
+    dval = dB = None
+    if ctx.needs_input_grad[3]:
+        t_rowptr, t_colind, perm = transpose(rowptr, colind, B.shape[0])
+        dB = _spmm(t_rowptr, t_colind, _gather(perm, val), dC, None, n_rows=B.shape[0]).to(B.dtype)
+    if ctx.needs_input_grad[2]:
+        dval = _sddmm(rowptr, colind, dC, B.float().contiguous())
+    return (None, None, dval, dB) + (None,) * (len(ctx.needs_input_grad) - 4)
+
+
+spmm_csr.register_autograd(_spmm_backward, setup_context=_spmm_setup)
+spmm_csr_split.register_autograd(_spmm_backward, setup_context=_spmm_setup)
+
+
+# ---------------------------------------------------------------------------- SDDMM ---
+@torch.library.custom_op("autosage::sddmm_csr", mutates_args=())
+def sddmm_csr(rowptr: torch.Tensor, colind: torch.Tensor, X: torch.Tensor, Y: torch.Tensor) -> torch.Tensor:
+    return _sddmm(rowptr, colind, X.contiguous(), Y.contiguous())
+
+
+@sddmm_csr.register_fake
+def _(rowptr, colind, X, Y):
+    return X.new_empty((colind.shape[0],), dtype=torch.float32)
+
+
+def _sddmm_setup(ctx, inputs, output):
+    ctx.save_for_backward(*inputs)
+
+
+def _sddmm_backward(ctx, dout):
+    rowptr, colind, X, Y = ctx.saved_tensors
+    dout = dout.contiguous()
+    dX = dY = None
+    if ctx.needs_input_grad[2]:       # dX_i = sum_p dout[p] Y_j
+        dX = _spmm(rowptr, colind, dout, Y.contiguous(), None).to(X.dtype)
+    if ctx.needs_input_grad[3]:       # dY_j = sum_{p: col = j} dout[p] X_i
+        t_rowptr, t_colind, perm = transpose(rowptr, colind, Y.shape[0])
+        dY = _spmm(t_rowptr, t_colind, _gather(perm, dout), X.contiguous(), None, n_rows=Y.shape[0]).to(Y.dtype)
+    return None, None, dX, dY
+
+
+sddmm_csr.register_autograd(_sddmm_backward, setup_context=_sddmm_setup)
+
+
+# -------------------------------------------------------------------------- softmax ---
+def _softmax_hub(rowptr):
+    return 1024          # rows this long are split; shorter graphs never reach it
+
+
+@torch.library.custom_op("autosage::csr_row_softmax", mutates_args=())
+def csr_row_softmax(rowptr: torch.Tensor, s: torch.Tensor) -> torch.Tensor:
+    h = handle(s.device)
+    s = s.contiguous()
+    n_rows, nnz = rowptr.numel() - 1, s.shape[0]
+    H = 1 if s.dim() == 1 else s.shape[1]
+    out = torch.zeros_like(s)            # entries of empty rows do not exist; zeros keep the result defined
+    hub = _softmax_hub(rowptr)
+    ws = _ws(h.workspace_bytes(ab.OP_SOFTMAX, n_rows, nnz, 1, H, ab.Schedule(hub_t=hub)), s.device)
+    h.csr_row_softmax(n_rows, nnz, rowptr, s, out, H=H, hub_t=hub, workspace=ws)
+    return out
+
+
+@csr_row_softmax.register_fake
+def _(rowptr, s):
+    return torch.empty_like(s)
+
+
+def _softmax_setup(ctx, inputs, output):
+    ctx.save_for_backward(inputs[0], output)
+
+
+def _softmax_backward(ctx, dP):
+    rowptr, P = ctx.saved_tensors
+    h = handle(P.device)
+    dP = dP.contiguous()
+    n_rows, nnz = rowptr.numel() - 1, P.shape[0]
+    H = 1 if P.dim() == 1 else P.shape[1]
+    dS = torch.empty_like(P)
+    hub = _softmax_hub(rowptr)
+    ws = _ws(h.workspace_bytes(ab.OP_SOFTMAX, n_rows, nnz, 1, H, ab.Schedule(hub_t=hub)), P.device)
+    h.csr_row_softmax_backward(n_rows, nnz, rowptr, P, dP, dS, H=H, hub_t=hub, workspace=ws)
+    return None, dS
+
+
+csr_row_softmax.register_autograd(_softmax_backward, setup_context=_softmax_setup)
+
+
+# ------------------------------------------------------------------------ attention ---
+@torch.library.custom_op("autosage::csr_attention_forward", mutates_args=())
+def csr_attention_forward(rowptr: torch.Tensor, colind: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
+                          scale: float) -> torch.Tensor:
+    _check_csr(rowptr, colind)
+    h = handle(Q.device)
+    Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
+    N, H, d = Q.shape
+    nnz = colind.numel()
+    O = torch.empty((N, H, d), dtype=torch.float32, device=Q.device)
+    ws = _ws(h.workspace_bytes(ab.OP_ATTENTION, N, nnz, d, H), Q.device)
+    h.csr_attention(N, rowptr, colind, Q, K, V, O, H, d, scale, in_dt=_dt(Q), workspace=ws, nnz=nnz)
+    return O
+
+
+@csr_attention_forward.register_fake
+def _(rowptr, colind, Q, K, V, scale):
+    return Q.new_empty(Q.shape, dtype=torch.float32)
+
+
+def _attention_setup(ctx, inputs, output):
+    rowptr, colind, Q, K, V, scale = inputs
+    ctx.save_for_backward(rowptr, colind, Q, K, V)
+    ctx.scale = scale
+
+
+def _attention_backward(ctx, dO):
+    """Head by head, with the library's operators on strided views of the [N, H, d] tensors:
+    S = scale * SDDMM(Q, K), P = softmax(S), dV = P^T dO, dP = SDDMM(dO, V), dS = softmax'(P, dP),
+    dQ = scale * dS K, dK = scale * dS^T Q.  (The probabilities are recomputed, not stored.)"""
+    rowptr, colind, Q, K, V = ctx.saved_tensors
+    scale = ctx.scale
+    N, H, d = Q.shape
+    Qf, Kf, Vf = (t.float().contiguous() for t in (Q, K, V))
+    dO = dO.float().contiguous()
+    t_rowptr, t_colind, perm = transpose(rowptr, colind, N)
+    dQ, dK, dV = (torch.empty((N, H, d), dtype=torch.float32, device=Q.device) for _ in range(3))
+    HD = H * d
+    for hd in range(H):
+        q, k, v, g = (t[:, hd, :] for t in (Qf, Kf, Vf, dO))           # views with leading dimension H*d
+        S = _sddmm(rowptr, colind, q, k, ldx=HD, ldy=HD, F=d)
+        S.mul_(scale)
+        P = csr_row_softmax(rowptr, S)
+        _spmm(t_rowptr, t_colind, _gather(perm, P), g, None, n_rows=N, ldb=HD, out=dV[:, hd, :], ldc=HD, F=d)
+        dP = _sddmm(rowptr, colind, g, v, ldx=HD, ldy=HD, F=d)
+        dS = _softmax_backward_raw(rowptr, P, dP)
+        dS.mul_(scale)
+        _spmm(rowptr, colind, dS, k, None, ldb=HD, out=dQ[:, hd, :], ldc=HD, F=d)
+        _spmm(t_rowptr, t_colind, _gather(perm, dS), q, None, n_rows=N, ldb=HD, out=dK[:, hd, :], ldc=HD, F=d)
+    return None, None, dQ.to(Q.dtype), dK.to(K.dtype), dV.to(V.dtype), None
+
+
+def _softmax_backward_raw(rowptr, P, dP):
+    h = handle(P.device)
+    n_rows, nnz = rowptr.numel() - 1, P.shape[0]
+    dS = torch.empty_like(P)
+    hub = _softmax_hub(rowptr)
+    ws = _ws(h.workspace_bytes(ab.OP_SOFTMAX, n_rows, nnz, 1, 1, ab.Schedule(hub_t=hub)), P.device)
+    h.csr_row_softmax_backward(n_rows, nnz, rowptr, P, dP, dS, H=1, hub_t=hub, workspace=ws)
+    return dS
+
+
+csr_attention_forward.register_autograd(_attention_backward, setup_context=_attention_setup)
+
+# the paper's name for the scheduler-routed SDDMM
+sddmm_csr_auto = sddmm_csr

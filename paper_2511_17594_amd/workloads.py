@@ -99,7 +99,9 @@ def distinct_columns(rng: np.random.Generator, deg: np.ndarray, n_cols: int,
     nnz = int(rowptr64[-1])
     if nnz >= 2**31:
         raise ValueError("nnz does not fit int32")
-    big = np.flatnonzero(deg >= big_row)
+    # rows that fill a good part of the column range are also drawn without replacement (the top-up
+    # of a nearly full row converges slowly)
+    big = np.flatnonzero(deg >= min(big_row, max(1, n_cols // 4)))
     small_deg = deg.copy()
     small_deg[big] = 0
 

@@ -1,0 +1,125 @@
+"""GPU parity of the adjoint helpers (CSR transpose, value gather, row-softmax backward) against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_17594_amd import workloads as W
+from util import dev, rel_l1_rows, rel_l1_segments
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    return torch
+
+
+@pytest.fixture(scope="module")
+def ab():
+    from paper_2511_17594_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def handle(ab):
+    h = ab.Handle(0)
+    yield h
+    h.close()
+
+
+def skew(n_rows, n_cols, seed):
+    rng = np.random.default_rng(seed)
+    deg = np.minimum(W.powerlaw_degrees(rng, n_rows, 2.1, 12.0, 2500), n_cols)
+    deg[3::53] = 0
+    return W.csr_from_degrees(rng, deg, n_cols)
+
+
+def gpu_transpose(torch, handle, A, with_val=True, keep_perm=True):
+    nnz = A.nnz
+    t_rowptr = torch.full((A.n_cols + 1,), -1, dtype=torch.int32, device="cuda")
+    t_colind = torch.full((max(nnz, 1),), -1, dtype=torch.int32, device="cuda")
+    t_val = torch.full((max(nnz, 1),), float("nan"), dtype=torch.float32, device="cuda") if with_val else None
+    perm = torch.full((max(nnz, 1),), -1, dtype=torch.int32, device="cuda") if keep_perm else None
+    ws = torch.empty(handle.csr_transpose_workspace_bytes(A.n_rows, A.n_cols, nnz), dtype=torch.uint8, device="cuda")
+    handle.csr_transpose(A.n_rows, A.n_cols, nnz, dev(A.rowptr, torch), dev(A.colind, torch),
+                         dev(A.val, torch) if with_val else None, t_rowptr, t_colind, t_val, perm, ws)
+    torch.cuda.synchronize()
+    return t_rowptr, t_colind, t_val, perm
+
+
+@pytest.mark.parametrize("n_rows,n_cols", [(5003, 5003), (3000, 777), (400, 9001)])
+def test_transpose_bit_exact(torch, handle, ab, n_rows, n_cols):
+    A = skew(n_rows, n_cols, n_rows)
+    o_ptr, o_col, o_val, o_perm = oracle.csr_transpose(A.rowptr, A.colind, A.val, A.n_cols)
+    t_rowptr, t_colind, t_val, perm = gpu_transpose(torch, handle, A)
+    assert np.array_equal(t_rowptr.cpu().numpy(), o_ptr)
+    assert np.array_equal(t_colind.cpu().numpy()[:A.nnz], o_col)
+    assert np.array_equal(perm.cpu().numpy()[:A.nnz], o_perm)
+    assert np.array_equal(t_val.cpu().numpy()[:A.nnz], o_val)
+    # pattern only, permutation kept inside the workspace
+    t_rowptr2, t_colind2, _, _ = gpu_transpose(torch, handle, A, with_val=False, keep_perm=False)
+    assert torch.equal(t_rowptr2, t_rowptr) and torch.equal(t_colind2, t_colind)
+    # gather carries per-nonzero rows of values (e.g. [nnz, H] probabilities) into the transposed order
+    vals = torch.randn(A.nnz, 3, device="cuda")
+    outv = torch.empty_like(vals)
+    handle.gather_values(A.nnz, 3, perm, vals, outv)
+    torch.cuda.synchronize()
+    assert torch.equal(outv, vals[perm[:A.nnz].long()])
+
+
+def test_transpose_degenerate(torch, handle, ab):
+    A = W.CSR(7, 5, np.zeros(8, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    t_rowptr, _, _, _ = gpu_transpose(torch, handle, A)
+    assert np.array_equal(t_rowptr.cpu().numpy(), np.zeros(6, np.int32))
+    # duplicates and unsorted columns keep storage order
+    A = W.CSR(3, 3, np.array([0, 2, 3, 5], np.int32), np.array([2, 0, 2, 2, 2], np.int32), np.arange(1, 6, dtype=np.float32))
+    t_rowptr, t_colind, t_val, perm = gpu_transpose(torch, handle, A)
+    assert t_rowptr.tolist() == [0, 1, 1, 5] and t_colind.tolist() == [0, 0, 1, 2, 2]
+    assert t_val.tolist() == [2, 1, 3, 4, 5] and perm.tolist() == [1, 0, 2, 3, 4]
+
+
+def test_spmm_adjoint_through_the_transpose(torch, handle, ab):
+    """d/dB of C = A B is A^T dC: SpMM on the transposed pattern against the oracle's definition."""
+    A = skew(4000, 2500, 5)
+    F = 48
+    rng = np.random.default_rng(1)
+    dC = rng.standard_normal((A.n_rows, F)).astype(np.float32)
+    t_rowptr, t_colind, t_val, _ = gpu_transpose(torch, handle, A)
+    dB = torch.full((A.n_cols, F), float("nan"), dtype=torch.float32, device="cuda")
+    s = ab.Schedule(mapping=ab.MAP_WAVE_ROW, hub_t=256, hub_chunk=256)
+    ws = torch.empty(handle.workspace_bytes(ab.OP_SPMM, A.n_cols, A.nnz, F, 1, s), dtype=torch.uint8, device="cuda")
+    handle.spmm(A.n_cols, A.n_rows, t_rowptr, t_colind, t_val, dev(dC, torch), dB, F, sched=s, workspace=ws, nnz=A.nnz)
+    torch.cuda.synchronize()
+    o_ptr, o_col, o_val, _ = oracle.csr_transpose(A.rowptr, A.colind, A.val, A.n_cols)
+    ref = oracle.spmm(o_ptr, o_col, o_val, dC)
+    ref_abs = oracle.spmm(o_ptr, o_col, np.abs(o_val), np.abs(dC))
+    assert rel_l1_rows(dB.cpu().numpy(), ref, ref_abs).max() <= 1e-5
+
+
+@pytest.mark.parametrize("H,hub_t", [(1, 0), (4, 0), (8, 128), (3, 64), (70, 256)])
+def test_softmax_backward(torch, handle, ab, H, hub_t):
+    A = skew(3001, 3001, 11)
+    rng = np.random.default_rng(H)
+    s = (2.0 * rng.standard_normal((A.nnz, H))).astype(np.float32)
+    P64 = oracle.row_softmax(A.rowptr, s)
+    P = P64.astype(np.float32)
+    dP = rng.standard_normal((A.nnz, H)).astype(np.float32)
+    ref = oracle.row_softmax_backward(A.rowptr, P, dP)
+    ref_abs = oracle.row_softmax_backward(A.rowptr, P, -np.abs(dP))      # all terms of one sign: magnitude of the terms
+    d_rp, d_P, d_dP = dev(A.rowptr, torch), dev(P, torch), dev(dP, torch)
+    dS = torch.full_like(d_dP, float("nan"))
+    ws = torch.empty(handle.workspace_bytes(ab.OP_SOFTMAX, A.n_rows, A.nnz, 1, H, ab.Schedule(hub_t=hub_t)), dtype=torch.uint8,
+                     device="cuda")
+    handle.csr_row_softmax_backward(A.n_rows, A.nnz, d_rp, d_P, d_dP, dS, H=H, hub_t=hub_t, workspace=ws)
+    torch.cuda.synchronize()
+    got = dS.cpu().numpy()
+    assert np.isfinite(got).all()
+    scale = np.abs(P.astype(np.float64)) * (np.abs(dP.astype(np.float64)) + np.abs(ref_abs / np.maximum(P64, 1e-300) + np.abs(dP)))
+    for h in range(H):
+        err = rel_l1_segments(got[:, h], ref[:, h], A.rowptr, scale[:, h])
+        assert err.max() <= 1e-5, (H, h, float(err.max()))
+    # in place on dP
+    handle.csr_row_softmax_backward(A.n_rows, A.nnz, d_rp, d_P, d_dP, d_dP, H=H, hub_t=hub_t, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_dP.cpu().numpy(), got)

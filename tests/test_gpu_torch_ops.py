@@ -1,0 +1,131 @@
+"""The torch.ops.autosage operators: forward values and autograd gradients against dense float64
+PyTorch CPU formulas (masked dense matmul / softmax / attention with autograd as the reference)."""
+import numpy as np
+import pytest
+
+from paper_2511_17594_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    return torch
+
+
+@pytest.fixture(scope="module")
+def ops(torch):
+    from paper_2511_17594_amd import torch_ops
+    return torch_ops
+
+
+@pytest.fixture(scope="module")
+def graph():
+    rng = np.random.default_rng(3)
+    n_rows, n_cols = 700, 900
+    deg = rng.poisson(5.0, n_rows)
+    deg[7] = 850                     # longer than a wavefront's index block many times over
+    deg[11] = 0
+    return W.csr_from_degrees(rng, deg, n_cols)
+
+
+def rel(a, b):
+    a, b = a.detach().double().cpu(), b.detach().double().cpu()
+    return float((a - b).abs().sum() / b.abs().sum().clamp_min(1e-30))
+
+
+def dense_of(torch, A, val):
+    rows = torch.from_numpy(np.repeat(np.arange(A.n_rows), A.degrees))
+    cols = torch.from_numpy(A.colind.astype(np.int64))
+    D = torch.zeros((A.n_rows, A.n_cols), dtype=torch.float64)
+    return D.index_put((rows, cols), val, accumulate=True), rows, cols
+
+
+def test_ops_are_registered(torch, ops):
+    for name in ("spmm_csr", "spmm_csr_split", "sddmm_csr", "csr_row_softmax", "csr_attention_forward"):
+        assert hasattr(torch.ops.autosage, name)
+
+
+@pytest.mark.parametrize("split", [False, True])
+def test_spmm_forward_and_gradients(torch, ops, graph, split):
+    A, F = graph, 24
+    g = torch.Generator().manual_seed(1)
+    val64 = torch.from_numpy(A.val.astype(np.float64)).requires_grad_(True)
+    B64 = torch.randn(A.n_cols, F, dtype=torch.float64, generator=g).requires_grad_(True)
+    Wt = torch.randn(A.n_rows, F, dtype=torch.float64, generator=g)
+    D, _, _ = dense_of(torch, A, val64)
+    (D @ B64 * Wt).sum().backward()
+    rp, ci = torch.from_numpy(A.rowptr).cuda(), torch.from_numpy(A.colind).cuda()
+    val = val64.detach().float().cuda().requires_grad_(True)
+    B = B64.detach().float().cuda().requires_grad_(True)
+    C = torch.ops.autosage.spmm_csr_split(rp, ci, val, B, 256) if split else torch.ops.autosage.spmm_csr(rp, ci, val, B)
+    assert rel(C, D @ B64) <= 1e-5
+    (C * Wt.float().cuda()).sum().backward()
+    assert rel(B.grad, B64.grad) <= 1e-5 and rel(val.grad, val64.grad) <= 1e-5
+
+
+def test_sddmm_forward_and_gradients(torch, ops, graph):
+    A, F = graph, 20
+    g = torch.Generator().manual_seed(2)
+    X64 = torch.randn(A.n_rows, F, dtype=torch.float64, generator=g).requires_grad_(True)
+    Y64 = torch.randn(A.n_cols, F, dtype=torch.float64, generator=g).requires_grad_(True)
+    w = torch.randn(A.nnz, dtype=torch.float64, generator=g)
+    _, rows, cols = dense_of(torch, A, torch.zeros(A.nnz, dtype=torch.float64))
+    ref = (X64[rows] * Y64[cols]).sum(dim=1)
+    (ref * w).sum().backward()
+    rp, ci = torch.from_numpy(A.rowptr).cuda(), torch.from_numpy(A.colind).cuda()
+    X = X64.detach().float().cuda().requires_grad_(True)
+    Y = Y64.detach().float().cuda().requires_grad_(True)
+    out = torch.ops.autosage.sddmm_csr(rp, ci, X, Y)
+    assert rel(out, ref) <= 1e-5
+    (out * w.float().cuda()).sum().backward()
+    assert rel(X.grad, X64.grad) <= 1e-5 and rel(Y.grad, Y64.grad) <= 1e-5
+
+
+def test_softmax_and_attention_gradients(torch, ops, graph):
+    rng = np.random.default_rng(5)
+    n = 600
+    deg = rng.poisson(6.0, n)
+    deg[5] = 580
+    deg[9] = 0
+    A = W.csr_from_degrees(rng, deg, n)
+    H, d, scale = 2, 16, 0.25
+    g = torch.Generator().manual_seed(3)
+    Q64, K64, V64 = (torch.randn(n, H, d, dtype=torch.float64, generator=g).requires_grad_(True) for _ in range(3))
+    Wt = torch.randn(n, H, d, dtype=torch.float64, generator=g)
+    mask = torch.zeros((n, n), dtype=torch.bool)
+    rows = torch.from_numpy(np.repeat(np.arange(n), A.degrees))
+    cols = torch.from_numpy(A.colind.astype(np.int64))
+    mask[rows, cols] = True
+    S = scale * torch.einsum("ihk,jhk->hij", Q64, K64)
+    S = S.masked_fill(~mask[None], float("-inf"))
+    P = torch.softmax(S, dim=2)
+    P = torch.nan_to_num(P, nan=0.0)                     # the empty row
+    O_ref = torch.einsum("hij,jhk->ihk", P, V64)
+    (O_ref * Wt).sum().backward()
+    rp, ci = torch.from_numpy(A.rowptr).cuda(), torch.from_numpy(A.colind).cuda()
+    Q, K, V = (t.detach().float().cuda().requires_grad_(True) for t in (Q64, K64, V64))
+    O = torch.ops.autosage.csr_attention_forward(rp, ci, Q, K, V, scale)
+    assert rel(O, O_ref) <= 2e-5
+    (O * Wt.float().cuda()).sum().backward()
+    assert rel(Q.grad, Q64.grad) <= 5e-5 and rel(K.grad, K64.grad) <= 5e-5 and rel(V.grad, V64.grad) <= 5e-5
+    # row-softmax alone, two heads
+    s64 = torch.randn(A.nnz, H, dtype=torch.float64, generator=g).requires_grad_(True)
+    w = torch.randn(A.nnz, H, dtype=torch.float64, generator=g)
+    dense = torch.full((H, n, n), float("-inf"), dtype=torch.float64)
+    dense = dense.index_put((torch.arange(H)[:, None], rows[None], cols[None]), s64.T)
+    Pd = torch.nan_to_num(torch.softmax(dense, dim=2), nan=0.0)
+    ref = Pd[:, rows, cols].T
+    (ref * w).sum().backward()
+    s = s64.detach().float().cuda().requires_grad_(True)
+    P_gpu = torch.ops.autosage.csr_row_softmax(rp, s)
+    assert rel(P_gpu, ref) <= 1e-5
+    (P_gpu * w.float().cuda()).sum().backward()
+    assert rel(s.grad, s64.grad) <= 1e-5
+    # bf16 operands: forward runs in the bf16 kernels, gradients come back in bf16
+    Qb, Kb, Vb = (t.detach().to(torch.bfloat16).cuda().requires_grad_(True) for t in (Q64, K64, V64))
+    Ob = torch.ops.autosage.csr_attention_forward(rp, ci, Qb, Kb, Vb, scale)
+    assert rel(Ob, O_ref) <= 2e-2
+    (Ob * Wt.float().cuda()).sum().backward()
+    assert Qb.grad.dtype == torch.bfloat16 and rel(Qb.grad, Q64.grad) <= 3e-2 and rel(Vb.grad, V64.grad) <= 3e-2
