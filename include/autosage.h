@@ -28,6 +28,12 @@
  *     Arguments are checked before anything is launched.
  *   - Outputs must not alias inputs (row-softmax may run in place).
  *   - For a fixed schedule the result is bit-reproducible: no floating-point atomics are used.
+ *   - A handle is not thread safe: use one handle per host thread (handles share nothing).
+ *   - The selector remembers the degree features of the last 16 (rowptr pointer, n_rows, n_cols, nnz)
+ *     combinations so that steady-state calls need no device-to-host copy.  Overwriting a rowptr array
+ *     in place with another graph of the same sizes therefore replays the old graph's decision (results
+ *     stay correct, the schedule may be a poor one); autosage_cache_clear or memoize_signature = 0
+ *     drops / disables that memory.
  */
 #ifndef AUTOSAGE_H
 #define AUTOSAGE_H

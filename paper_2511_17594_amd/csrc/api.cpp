@@ -243,13 +243,13 @@ StageTimer::StageTimer(autosage_ctx* h, const char* stage, hipStream_t st) : h_(
     }
     autosage_ctx::StageSpan& s = h_->spans[h_->spans_used++];
     s.stage = stage;
-    hipEventRecord(s.start, st_);
+    (void)hipEventRecord(s.start, st_);
     stop_ = s.stop;
 }
 
 StageTimer::~StageTimer()
 {
-    if (stop_) hipEventRecord(stop_, st_);
+    if (stop_) (void)hipEventRecord(stop_, st_);
 }
 
 #define STAGE(h, name, st, call)      \
@@ -327,7 +327,7 @@ extern "C" autosage_status_t autosage_create(autosage_handle_t* out, int device_
             return AUTOSAGE_ERR_HIP;
         }
         int rt = 0;
-        hipRuntimeGetVersion(&rt);
+        (void)hipRuntimeGetVersion(&rt);
         h->cu_count = prop.multiProcessorCount;
         char buf[256];
         std::snprintf(buf, sizeof buf, "%s_%dcu_hip%d_lib1", prop.gcnArchName, prop.multiProcessorCount, rt);
@@ -356,14 +356,14 @@ extern "C" autosage_status_t autosage_destroy(autosage_handle_t h)
     if (!h) return AUTOSAGE_ERR_INVALID_ARG;
     autosage_status_t st = AUTOSAGE_OK;
     if (!h->cache_path.empty()) st = autosage_cache_save(h, h->cache_path.c_str());
-    if (h->dev_features) hipFree(h->dev_features);
-    if (h->host_features) hipHostFree(h->host_features);
-    if (h->dev_flag) hipFree(h->dev_flag);
-    if (h->ev0) hipEventDestroy(h->ev0);
-    if (h->ev1) hipEventDestroy(h->ev1);
+    if (h->dev_features) (void)hipFree(h->dev_features);
+    if (h->host_features) (void)hipHostFree(h->host_features);
+    if (h->dev_flag) (void)hipFree(h->dev_flag);
+    if (h->ev0) (void)hipEventDestroy(h->ev0);
+    if (h->ev1) (void)hipEventDestroy(h->ev1);
     for (auto& s : h->spans) {
-        if (s.start) hipEventDestroy(s.start);
-        if (s.stop) hipEventDestroy(s.stop);
+        if (s.start) (void)hipEventDestroy(s.start);
+        if (s.stop) (void)hipEventDestroy(s.stop);
     }
     delete h;
     return st;
@@ -476,6 +476,11 @@ extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, 
     Resolved r;
     autosage_status_t s = resolve_schedule(*sched, AUTOSAGE_OP_SPMM, F, dt, 1, common_alignment(B, ldb, esize),
                                            common_alignment(C, ldc, 4), &r);
+    if (s == AUTOSAGE_ERR_UNSUPPORTED && sched == &chosen) {
+        // a replayed decision was made for other strides or alignments: the baseline always applies
+        chosen = baseline_schedule();
+        s = resolve_schedule(chosen, AUTOSAGE_OP_SPMM, F, dt, 1, common_alignment(B, ldb, esize), common_alignment(C, ldc, 4), &r);
+    }
     if (s != AUTOSAGE_OK) return s;
     SpmmArgs a{};
     a.rows = RowMap{0, 1, (int32_t)n_rows, 0};
@@ -519,6 +524,10 @@ extern "C" autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows,
     if (al2 < al) al = al2;
     Resolved r;
     autosage_status_t s = resolve_schedule(*sched, AUTOSAGE_OP_SDDMM, F, dt, 1, al, 16, &r);
+    if (s == AUTOSAGE_ERR_UNSUPPORTED && sched == &chosen) {
+        chosen = baseline_schedule();          // replayed decision made for other strides or alignments
+        s = resolve_schedule(chosen, AUTOSAGE_OP_SDDMM, F, dt, 1, al, 16, &r);
+    }
     if (s != AUTOSAGE_OK) return s;
     SddmmArgs a{};
     a.rows = RowMap{0, 1, (int32_t)n_rows, 0};

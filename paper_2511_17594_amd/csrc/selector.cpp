@@ -582,6 +582,11 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
         }
     }
 
+    {
+        // the baseline must be able to run on this input: report its own error (e.g. a short workspace)
+        const autosage_status_t rc = run_once(h, in, sample, base, workspace, workspace_bytes, st);
+        if (rc != AUTOSAGE_OK) return rc;
+    }
     const double tb = time_schedule(h, in, sample, base, workspace, workspace_bytes, st, h->params.probe_iters,
                                     h->params.probe_cap_ms);
     if (!std::isfinite(tb)) return AUTOSAGE_ERR_HIP;

@@ -173,3 +173,28 @@ def test_attention_decision(torch, ab, graph):
     h.decide_attention(A.n_rows, rp, ci, dev(Q2, torch), dev(K2, torch), dev(V2, torch), O2, 2, d, scale, workspace=ws)
     assert h.last_decision()["cache_hit"] is False
     h.close()
+
+
+def test_replayed_decision_falls_back_when_alignment_changes(torch, ab, graph):
+    A, F = graph, 64
+    B, _ = ops(torch, ab, A, F, seed=9)
+    h = ab.Handle(0)
+    rp, ci, va = (dev(t, torch) for t in (A.rowptr, A.colind, A.val))
+    C = torch.empty((A.n_rows, F), dtype=torch.float32, device="cuda")
+    ws = torch.empty(h.workspace_bytes(ab.OP_SPMM, A.n_rows, A.nnz, F), dtype=torch.uint8, device="cuda")
+    dB = dev(B, torch)
+    h.spmm(A.n_rows, A.n_cols, rp, ci, va, dB, C, F, workspace=ws)
+    assert h.last_decision()["choice"]["vec_bytes"] == 16
+    # the same graph and width with a dense operand that is only 4-byte aligned: the cached 16-byte schedule
+    # cannot run, the call silently uses the baseline and stays correct
+    flat = torch.empty(A.n_cols * F + 1, dtype=torch.float32, device="cuda")
+    Bm = flat[1:].view(A.n_cols, F)
+    Bm.copy_(dB)
+    C2 = torch.full_like(C, float("nan"))
+    h.spmm(A.n_rows, A.n_cols, rp, ci, va, Bm, C2, F, workspace=ws)
+    assert h.last_decision()["cache_hit"] is True
+    torch.cuda.synchronize()
+    ref = oracle.spmm(A.rowptr, A.colind, A.val, B)
+    ref_abs = oracle.spmm(A.rowptr, A.colind, np.abs(A.val), np.abs(B))
+    assert rel_l1_rows(C2.cpu().numpy(), ref, ref_abs).max() <= 1e-5
+    h.close()
