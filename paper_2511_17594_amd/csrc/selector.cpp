@@ -162,7 +162,9 @@ void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, in
                         s.vec_bytes = vb;
                         s.unroll = u;
                         s.hub_t = p.force_hub_t >= 0 ? p.force_hub_t : hub;
-                        s.hub_chunk = s.hub_t;
+                        // SpMM chunks carry a reduction and a partial row each: four thresholds per chunk amortise
+                        // them; SDDMM chunks are independent, the threshold itself balances best
+                        s.hub_chunk = op == AUTOSAGE_OP_SPMM ? 4 * s.hub_t : s.hub_t;
                         s.xcd_remap = xcd;
                         Resolved r;
                         if (resolve_schedule(s, op, F, dt, 1, align_bytes, align_bytes, &r) != AUTOSAGE_OK) continue;
@@ -445,7 +447,7 @@ static void shortlist_attention(const autosage_ctx* h, int64_t nnz, const int64_
             s.mapping = fused ? AUTOSAGE_MAP_FUSED : AUTOSAGE_MAP_WAVE_ROW;
             s.waves_per_wg = h->params.force_wpb > 0 ? h->params.force_wpb : 4;
             s.hub_t = h->params.force_hub_t >= 0 ? h->params.force_hub_t : hub;
-            s.hub_chunk = s.hub_t;
+            s.hub_chunk = fused ? 4 * s.hub_t : s.hub_t;     // a chunk of the single pass carries a state merge
             double t = nnz * row_bytes / bw + (fused ? 0.0 : 16.0 * H * nnz / bw + 2 * t_launch);
             const double longest = s.hub_t > 0 ? std::min<double>((double)max_deg, s.hub_t) : (double)max_deg;
             t = std::max(t, longest / 4.0 * t_step * (fused ? 1.0 : 2.0));
