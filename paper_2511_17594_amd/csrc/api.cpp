@@ -761,7 +761,7 @@ extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autos
                                                       const autosage_schedule_t* sched, size_t* bytes)
 {
     if (!h || !bytes || !sizes_ok(n_rows, 0, nnz) || F <= 0 || H <= 0) return AUTOSAGE_ERR_INVALID_ARG;
-    int hub_t = kSelectorMinHubT, chunk = kSelectorMinHubT;
+    int hub_t = kSelectorMinHubT, chunk = kSelectorMinChunk;
     if (sched) {
         hub_t = sched->hub_t;
         chunk = sched->hub_t > 0 ? (sched->hub_chunk > 0 ? sched->hub_chunk : sched->hub_t) : 0;

@@ -99,7 +99,8 @@ struct autosage_ctx {
 namespace autosage {
 
 constexpr int kMinHubT = 64;               // smallest split threshold the library accepts
-constexpr int kSelectorMinHubT = 512;      // smallest threshold the selector proposes
+constexpr int kSelectorMinHubT = 512;      // smallest threshold the selector proposes for SpMM / SDDMM
+constexpr int kSelectorMinChunk = 256;     // shortest hub chunk the selector proposes
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

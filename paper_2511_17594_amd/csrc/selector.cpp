@@ -78,6 +78,23 @@ struct Model {
     int waves = 8192;              // resident wavefronts (256 CUs x 4 SIMDs x 8)
 };
 
+// Chunk length for the rows at or above hub_t: `factor` thresholds per chunk where the histogram
+// promises enough chunks to occupy the chip (about eight workgroups per compute unit), halved down to
+// kSelectorMinChunk nonzeros where the hub rows are few.
+int pick_hub_chunk(const int64_t* hist, int64_t max_deg, int hub_t, int factor, int cu_count)
+{
+    if (hub_t <= 0) return 0;
+    double hub_nnz = 0.0;
+    for (int b = 1; b < 33; ++b) {
+        const double lo = std::ldexp(1.0, b - 1);
+        if (lo >= hub_t) hub_nnz += std::min<double>(1.5 * lo, (double)max_deg) * (double)hist[b];
+    }
+    const double want = 8.0 * (cu_count > 0 ? cu_count : 256);
+    int chunk = factor * hub_t;
+    while (chunk > kSelectorMinChunk && hub_nnz / chunk < want) chunk >>= 1;
+    return std::max(chunk, kSelectorMinChunk);
+}
+
 double estimate_one(const Model& m, int op, int64_t n_rows, int64_t nnz, const int64_t* hist, int64_t max_deg, int32_t F,
                     int esize, const Resolved& r)
 {
@@ -164,7 +181,8 @@ void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, in
                         s.hub_t = p.force_hub_t >= 0 ? p.force_hub_t : hub;
                         // SpMM chunks carry a reduction and a partial row each: four thresholds per chunk amortise
                         // them; SDDMM chunks are independent, the threshold itself balances best
-                        s.hub_chunk = op == AUTOSAGE_OP_SPMM ? 4 * s.hub_t : s.hub_t;
+                        s.hub_chunk = pick_hub_chunk(hist33, max_deg, s.hub_t, op == AUTOSAGE_OP_SPMM ? 4 : 1,
+                                                     h ? h->cu_count : 0);
                         s.xcd_remap = xcd;
                         Resolved r;
                         if (resolve_schedule(s, op, F, dt, 1, align_bytes, align_bytes, &r) != AUTOSAGE_OK) continue;
@@ -389,16 +407,22 @@ autosage_status_t run_once(autosage_ctx* h, const OpInput& in, const RowMap& row
 // Median of up to `iters` timed runs after one warm-up run; stops early once the timed runs add up
 // to cap_ms.  The warm-up is timed as well: when it alone takes four caps or more (a slow schedule
 // on this input) it is returned as the measurement, since cold-start effects are negligible at that
-// length and repeating it would only burn time.  Returns +inf when the schedule cannot run.
+// length and repeating it would only burn time.  Returns +inf when the schedule cannot run; `why`
+// (optional) then holds the status of the run that failed.
 double time_schedule(autosage_ctx* h, const OpInput& in, const RowMap& rows, const autosage_schedule_t& s, void* ws,
-                     size_t ws_bytes, hipStream_t st, int iters, double cap_ms)
+                     size_t ws_bytes, hipStream_t st, int iters, double cap_ms, autosage_status_t* why = nullptr)
 {
     const double inf = std::numeric_limits<double>::infinity();
     std::vector<double> t;
     double total = 0.0;
+    if (why) *why = AUTOSAGE_ERR_HIP;
     for (int i = -1; i < iters; ++i) {
         if (hipEventRecord(h->ev0, st) != hipSuccess) return inf;
-        if (run_once(h, in, rows, s, ws, ws_bytes, st) != AUTOSAGE_OK) return inf;
+        const autosage_status_t rc = run_once(h, in, rows, s, ws, ws_bytes, st);
+        if (rc != AUTOSAGE_OK) {
+            if (why) *why = rc;
+            return inf;
+        }
         if (hipEventRecord(h->ev1, st) != hipSuccess) return inf;
         if (hipEventSynchronize(h->ev1) != hipSuccess) return inf;
         float ms = 0.f;
@@ -447,7 +471,8 @@ static void shortlist_attention(const autosage_ctx* h, int64_t nnz, const int64_
             s.mapping = fused ? AUTOSAGE_MAP_FUSED : AUTOSAGE_MAP_WAVE_ROW;
             s.waves_per_wg = h->params.force_wpb > 0 ? h->params.force_wpb : 4;
             s.hub_t = h->params.force_hub_t >= 0 ? h->params.force_hub_t : hub;
-            s.hub_chunk = fused ? 4 * s.hub_t : s.hub_t;     // a chunk of the single pass carries a state merge
+            // a chunk of the single pass carries a state merge
+            s.hub_chunk = pick_hub_chunk(hist, max_deg, s.hub_t, fused ? 4 : 1, h->cu_count);
             double t = nnz * row_bytes / bw + (fused ? 0.0 : 16.0 * H * nnz / bw + 2 * t_launch);
             const double longest = s.hub_t > 0 ? std::min<double>((double)max_deg, s.hub_t) : (double)max_deg;
             t = std::max(t, longest / 4.0 * t_step * (fused ? 1.0 : 2.0));
@@ -584,14 +609,11 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
         }
     }
 
-    {
-        // the baseline must be able to run on this input: report its own error (e.g. a short workspace)
-        const autosage_status_t rc = run_once(h, in, sample, base, workspace, workspace_bytes, st);
-        if (rc != AUTOSAGE_OK) return rc;
-    }
+    // the baseline must be able to run on this input: report its own error (e.g. a short workspace)
+    autosage_status_t base_rc = AUTOSAGE_OK;
     const double tb = time_schedule(h, in, sample, base, workspace, workspace_bytes, st, h->params.probe_iters,
-                                    h->params.probe_cap_ms);
-    if (!std::isfinite(tb)) return AUTOSAGE_ERR_HIP;
+                                    h->params.probe_cap_ms, &base_rc);
+    if (!std::isfinite(tb)) return base_rc;
     std::vector<double> tc(topk);
     js << ",\"cache_hit\":false,\"replay_miss\":false,\"probe_rows\":" << sample.count << ",\"probe_stride\":" << stride
        << ",\"t_baseline_ms\":" << num(tb) << ",\"candidates\":[";
@@ -613,10 +635,14 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
         const RowMap full{0, 1, (int32_t)n_rows, 0};
         const double cap = std::numeric_limits<double>::infinity();
         const double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, cap);
-        // a baseline run that already takes more than twice the choice settles the question in one run
-        const double tf_b = time_schedule(h, in, full, base, workspace, workspace_bytes, st, 2, 0.5 * tf_c);
+        // The sample is a subset of the rows, so the baseline needs at least its sample time on the whole
+        // input: when that bound already covers the choice's full-input time the baseline is not run again.
+        // Otherwise a baseline run that takes more than twice the choice settles the question in one run.
+        const bool bound_settles = sample.count < n_rows && tb >= tf_c;
+        const double tf_b = bound_settles ? tb : time_schedule(h, in, full, base, workspace, workspace_bytes, st, 2, 0.5 * tf_c);
         const bool demote = !(tf_c <= tf_b);
-        js << ",\"confirm\":{\"t_choice_ms\":" << num(tf_c) << ",\"t_baseline_ms\":" << num(tf_b) << ",\"demoted\":"
+        js << ",\"confirm\":{\"t_choice_ms\":" << num(tf_c) << ",\"t_baseline_ms\":" << num(tf_b)
+           << ",\"baseline_bound_from_sample\":" << (bound_settles ? "true" : "false") << ",\"demoted\":"
            << (demote ? "true" : "false") << "}";
         if (demote) {
             choice = -1;
