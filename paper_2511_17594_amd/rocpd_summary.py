@@ -2,6 +2,7 @@
 
     python -m paper_2511_17594_amd.rocpd_summary kernels  <kernel-trace .db>
     python -m paper_2511_17594_amd.rocpd_summary counters <FETCH_SIZE .db> <WRITE_SIZE .db> [--traffic-out FILE]
+    python -m paper_2511_17594_amd.rocpd_summary fetch    <FETCH_SIZE .db>
 
 `kernels` prints calls / total / average duration per kernel from the profiler's per-dispatch begin and
 end times, and the average over the last `--last` dispatches of each kernel: the selector's cold calls
@@ -10,6 +11,7 @@ launch the same kernels on row samples, so only the trailing dispatches are the 
 `bench.py --copy-calibration` issues (1 GiB read and 1 GiB written per copy), prints the HBM bytes per
 launch of every kernel (mean over its last `--last` dispatches, the full-input ones), and with
 `--traffic-out` writes the "stage bytes" lines that `bench.py` reports as `roofline.traffic`.
+`fetch` is the read half alone (one profiler run), with the rate each kernel fetched at.
 Reads only; runs on the CPU.
 """
 from __future__ import annotations
@@ -101,6 +103,22 @@ def counter_report(fetch_path, write_path, last):
     return "\n".join(out), traffic
 
 
+def fetch_report(fetch_path, last):
+    fetch = counter_samples(fetch_path)
+    bf = bytes_per_unit(fetch)
+    out = ["bytes per FETCH_SIZE unit (from the 1 GiB copy): %.1f" % bf, "",
+           "FETCH_SIZE and ms are means over the last %d launches of each kernel." % last, "",
+           "| kernel | launches | FETCH_SIZE | HBM read MB | ms | read GB/s |", "|---|---|---|---|---|---|"]
+    for (k, _), l in fetch.items():
+        if "plain" in k or "copyBuffer" in k or "at::" in k or len(l) < last:
+            continue
+        tail = l[-last:]
+        fm = sum(v for v, _ in tail) / len(tail)
+        dm = sum(d for _, d in tail) / len(tail) / 1e6
+        out.append("| `%s` | %d | %.0f | %.1f | %.4f | %.0f |" % (k, len(l), fm, fm * bf / 1e6, dm, fm * bf / dm / 1e6))
+    return "\n".join(out)
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -112,7 +130,13 @@ def main(argv=None):
     c.add_argument("write_db")
     c.add_argument("--traffic-out", default=None)
     c.add_argument("--last", type=int, default=5, help="dispatches per kernel that belong to the timed steps")
+    f = sub.add_parser("fetch")
+    f.add_argument("db")
+    f.add_argument("--last", type=int, default=5)
     args = ap.parse_args(argv)
+    if args.cmd == "fetch":
+        print(fetch_report(args.db, args.last))
+        return
     if args.cmd == "kernels":
         print(kernel_table(args.db, args.last))
         return
