@@ -192,6 +192,14 @@ autosage_status_t autosage_graph_features(autosage_handle_t h, int64_t n_rows, i
 autosage_status_t autosage_validate_csr(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
                                         const int32_t* rowptr, const int32_t* colind, void* stream);
 
+/* 64-bit CSR index arrays (the default of many frameworks) enter through this call: dst[i] = src[i]
+ * for i < n as int32, on the device.  The kernels index with int32 (every workload of the paper's
+ * evaluation has nnz < 2^31); a value outside [0, limit] (limit <= INT32_MAX: nnz for a row-pointer
+ * array, n_cols - 1 for column indices) returns AUTOSAGE_ERR_UNSUPPORTED and leaves dst unspecified.
+ * src and dst are device arrays of n elements that do not overlap.  Synchronises the stream. */
+autosage_status_t autosage_narrow_indices(autosage_handle_t h, int64_t n, const int64_t* src, int32_t* dst,
+                                          int64_t limit, void* stream);
+
 /* ---- selector -------------------------------------------------------------------------- */
 
 /* Shortlist (Scheduler: "shortlist candidates with a roofline-style estimate").  Host only.

@@ -60,6 +60,7 @@ def _load():
         "autosage_graph_features": [vp, i64, i64, vp, c.POINTER(i64), c.POINTER(i64), c.POINTER(i64),
                                     c.POINTER(c.c_uint64), vp],
         "autosage_validate_csr": [vp, i64, i64, i64, vp, vp, vp],
+        "autosage_narrow_indices": [vp, i64, vp, vp, i64, vp],
         "autosage_shortlist": [vp, c.c_int, i64, i64, i64, c.POINTER(i64), i64, i32, c.c_int, i32, sp,
                                c.POINTER(c.c_double), i32, c.POINTER(i32)],
         "autosage_decide_from_times": [i32, c.POINTER(c.c_double), c.c_double, c.c_double, c.POINTER(i32)],
@@ -251,6 +252,12 @@ class Handle:
         raise AutosageError(st, "autosage_validate_csr")
 
     # -- selector ----------------------------------------------------------------------
+    def narrow_indices(self, src, dst, limit: int, stream=None):
+        """dst (int32) = src (int64) on the device; raises when a value lies outside [0, limit]."""
+        n = int(src.numel())
+        _check(_lib.autosage_narrow_indices(self._h, n, _ptr(src), _ptr(dst), int(limit), _stream(stream)),
+               "autosage_narrow_indices")
+
     def shortlist(self, op, n_rows, n_cols, nnz, hist33, max_deg, F, dt=F32, align_bytes=16, max_out=64):
         """Host only.  Returns [(Schedule, estimated seconds), ...] in ascending estimated time."""
         hist = (ctypes.c_int64 * 33)(*[int(x) for x in hist33])

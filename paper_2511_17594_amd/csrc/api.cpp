@@ -859,6 +859,19 @@ extern "C" autosage_status_t autosage_validate_csr(autosage_handle_t h, int64_t 
     return flag ? AUTOSAGE_ERR_INVALID_ARG : AUTOSAGE_OK;
 }
 
+extern "C" autosage_status_t autosage_narrow_indices(autosage_handle_t h, int64_t n, const int64_t* src, int32_t* dst,
+                                                     int64_t limit, void* stream)
+{
+    if (!h || n < 0 || limit < 0 || limit > INT32_MAX || (n > 0 && (!src || !dst))) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(launch_narrow_indices(n, src, dst, limit, h->dev_flag, st));
+    int32_t flag = 0;
+    HIP_TRY(hipMemcpyAsync(&flag, h->dev_flag, sizeof flag, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    return flag ? AUTOSAGE_ERR_UNSUPPORTED : AUTOSAGE_OK;
+}
+
 // ------------------------------------------------------------------------------------------
 // telemetry
 // ------------------------------------------------------------------------------------------

@@ -171,6 +171,8 @@ hipError_t launch_softmax_hub(const SoftmaxArgs& a, int32_t hub_chunk, const Hub
 // (int64[33 + 2 + 1024]); the caller copies it back.
 hipError_t launch_graph_features(int64_t n_rows, const int32_t* rowptr, int64_t* dev_out, hipStream_t stream);
 // CSR consistency check; dev_flag[0] becomes nonzero when a violation is found.
+hipError_t launch_narrow_indices(int64_t n, const int64_t* src, int32_t* dst, int64_t limit, int32_t* dev_flag,
+                                 hipStream_t stream);
 hipError_t launch_validate_csr(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
                                const int32_t* colind, int32_t* dev_flag, hipStream_t stream);
 

@@ -5,6 +5,7 @@
 // feature extraction uses row/nnz counts and the degree distribution.  The chunk scheme for
 // heavy rows (ceil(deg / hub_chunk) pieces of consecutive nonzeros) belongs to this library.
 #include "device_utils.h"
+#include <algorithm>
 #include "launch.h"
 
 namespace autosage {
@@ -190,6 +191,20 @@ __global__ void __launch_bounds__(256) validate_kernel(int64_t n_rows, int64_t n
 
 __global__ void zero_flag_kernel(int32_t* flag) { *flag = 0; }
 
+// dst[i] = (int32) src[i]; flags any value outside [0, limit]
+__global__ void __launch_bounds__(256) narrow_kernel(int64_t n, const int64_t* __restrict__ src, int32_t* __restrict__ dst,
+                                                     int64_t limit, int32_t* flag)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        const int64_t v = src[i];
+        bad |= v < 0 || v > limit;
+        dst[i] = static_cast<int32_t>(v);
+    }
+    if (bad) atomicOr(flag, 1);
+}
+
 }  // namespace
 
 hipError_t launch_hub_partition(const RowMap& rows, const int32_t* rowptr, int32_t hub_t, int32_t hub_chunk,
@@ -237,6 +252,17 @@ hipError_t launch_validate_csr(int64_t n_rows, int64_t n_cols, int64_t nnz, cons
     if (blocks < 1) blocks = 1;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(validate_kernel, dim3(blocks), dim3(256), 0, stream, n_rows, n_cols, nnz, rowptr, colind, dev_flag);
+    return hipGetLastError();
+}
+
+hipError_t launch_narrow_indices(int64_t n, const int64_t* src, int32_t* dst, int64_t limit, int32_t* dev_flag,
+                                 hipStream_t stream)
+{
+    hipLaunchKernelGGL(zero_flag_kernel, dim3(1), dim3(1), 0, stream, dev_flag);
+    if (n > 0) {
+        int blocks = (int)std::min<int64_t>((n + 255) / 256, 8192);
+        hipLaunchKernelGGL(narrow_kernel, dim3(blocks), dim3(256), 0, stream, n, src, dst, limit, dev_flag);
+    }
     return hipGetLastError();
 }
 

@@ -52,6 +52,21 @@ def _check_csr(rowptr, colind):
         raise TypeError("rowptr and colind must be int32 CUDA tensors")
 
 
+def csr_indices_int32(rowptr: torch.Tensor, colind: torch.Tensor, n_cols: int):
+    """int32 copies of int64 CSR index tensors (what `torch.sparse_csr_tensor` holds by default), made on the
+    device by the library; raises when an index does not fit the 32-bit kernels.  int32 inputs pass through."""
+    if rowptr.dtype == torch.int32 and colind.dtype == torch.int32:
+        return rowptr, colind
+    if rowptr.dtype != torch.int64 or colind.dtype != torch.int64 or not rowptr.is_cuda or not colind.is_cuda:
+        raise TypeError("rowptr and colind must both be int32 or both be int64 CUDA tensors")
+    h = handle(rowptr.device)
+    rp = torch.empty(rowptr.numel(), dtype=torch.int32, device=rowptr.device)
+    ci = torch.empty(colind.numel(), dtype=torch.int32, device=colind.device)
+    h.narrow_indices(rowptr.contiguous(), rp, colind.numel())
+    h.narrow_indices(colind.contiguous(), ci, max(n_cols - 1, 0))
+    return rp, ci
+
+
 def _spmm(rowptr, colind, val, B, sched, n_rows=None, ldb=None, out=None, ldc=None, F=None):
     _check_csr(rowptr, colind)
     h = handle(B.device)

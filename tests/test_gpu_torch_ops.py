@@ -129,3 +129,30 @@ def test_softmax_and_attention_gradients(torch, ops, graph):
     assert rel(Ob, O_ref) <= 2e-2
     (Ob * Wt.float().cuda()).sum().backward()
     assert Qb.grad.dtype == torch.bfloat16 and rel(Qb.grad, Q64.grad) <= 3e-2 and rel(Vb.grad, V64.grad) <= 3e-2
+
+
+def test_int64_indices_enter_through_the_narrowing_call(torch, ops, graph):
+    """64-bit CSR index tensors are narrowed on the device: equal to the int32 originals bit for bit, and a
+    value that does not fit the stated limit is an error, not a truncation."""
+    from paper_2511_17594_amd import binding as ab
+    A = graph
+    rp64 = torch.from_numpy(A.rowptr.astype(np.int64)).cuda()
+    ci64 = torch.from_numpy(A.colind.astype(np.int64)).cuda()
+    rp, ci = ops.csr_indices_int32(rp64, ci64, A.n_cols)
+    assert rp.dtype == torch.int32 and ci.dtype == torch.int32
+    assert np.array_equal(rp.cpu().numpy(), A.rowptr) and np.array_equal(ci.cpu().numpy(), A.colind)
+    same = ops.csr_indices_int32(rp, ci, A.n_cols)
+    assert same[0] is rp and same[1] is ci
+    with pytest.raises(ab.AutosageError):
+        ops.csr_indices_int32(rp64, ci64, int(A.colind.max()))          # n_cols one too small for the largest column
+    bad = rp64.clone()
+    bad[3] = 2 ** 31 + 5
+    with pytest.raises(ab.AutosageError):
+        ops.csr_indices_int32(bad, ci64, A.n_cols)
+    neg = ci64.clone()
+    neg[0] = -1
+    with pytest.raises(ab.AutosageError):
+        ops.csr_indices_int32(rp64, neg, A.n_cols)
+    empty = ops.csr_indices_int32(torch.zeros(1, dtype=torch.int64, device="cuda"),
+                                  torch.zeros(0, dtype=torch.int64, device="cuda"), 5)
+    assert empty[0].tolist() == [0] and empty[1].numel() == 0
