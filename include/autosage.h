@@ -74,6 +74,10 @@ typedef enum {
     AUTOSAGE_MAP_FUSED = 3       /* CSR attention only: one pass with a running softmax, no score array */
 } autosage_mapping_t;
 
+/* Most nonzeros, and most rows, of one call: 2^31 - 2^20.  Positions and row numbers are int32 inside the
+ * kernels and are stepped by at most one hub chunk past the end of a row. */
+#define AUTOSAGE_MAX_NNZ 2146435072LL
+
 /* A schedule = one point of the knob space (feature tile, mapping, vector width, hub split). */
 typedef struct {
     int32_t mapping;       /* autosage_mapping_t */
@@ -82,7 +86,7 @@ typedef struct {
     int32_t vec_bytes;     /* bytes per lane load: 4, 8 or 16; 0 = widest legal for F, ld and pointer alignment */
     int32_t unroll;        /* nonzeros in flight per lane group: 1, 2, 4 or 8; 0 = library default */
     int32_t hub_t;         /* rows with degree >= hub_t are split over workgroups; 0 = no hub split */
-    int32_t hub_chunk;     /* nonzeros per hub chunk; 0 = hub_t */
+    int32_t hub_chunk;     /* nonzeros per hub chunk, 64 .. 2^20; 0 = min(hub_t, 2^20) */
     int32_t xcd_remap;     /* 1 = consecutive row blocks stay on one XCD (contiguous row range per L2) */
 } autosage_schedule_t;
 
@@ -110,7 +114,7 @@ autosage_status_t autosage_get_param(autosage_handle_t h, const char* name, doub
 /* SpMM (Notation: C = A B).  C[n_rows, F] (fp32, dev) = A[n_rows, n_cols] * B[n_cols, F] (dt, dev).
  * rowptr[n_rows+1], colind[nnz], val[nnz] are dev pointers.  Empty rows give zero rows.
  * sched == NULL: the selector chooses (cache -> probe -> guardrail); else the given schedule runs.
- * Errors: INVALID_ARG (null pointer, F <= 0, ld < F, nnz >= 2^31, bad schedule field),
+ * Errors: INVALID_ARG (null pointer, F <= 0, ld < F, nnz or n_rows above AUTOSAGE_MAX_NNZ, bad schedule field),
  * UNSUPPORTED (vec_bytes illegal for this F / alignment), WORKSPACE_TOO_SMALL, HIP. */
 autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
                                 const int32_t* rowptr, const int32_t* colind, const float* val,

@@ -76,8 +76,8 @@ autosage_status_t resolve_schedule(const autosage_schedule_t& s, int op, int32_t
     if (!(r.unroll == 1 || r.unroll == 2 || r.unroll == 4 || r.unroll == 8)) return AUTOSAGE_ERR_INVALID_ARG;
     if (s.hub_t < 0 || s.hub_chunk < 0 || (s.hub_t > 0 && s.hub_t < kMinHubT)) return AUTOSAGE_ERR_INVALID_ARG;
     r.hub_t = s.hub_t;
-    r.hub_chunk = s.hub_t > 0 ? (s.hub_chunk > 0 ? s.hub_chunk : s.hub_t) : 0;
-    if (r.hub_t > 0 && r.hub_chunk < kMinHubT) return AUTOSAGE_ERR_INVALID_ARG;
+    r.hub_chunk = effective_hub_chunk(s.hub_t, s.hub_chunk);
+    if (r.hub_t > 0 && (r.hub_chunk < kMinHubT || r.hub_chunk > kMaxHubChunk)) return AUTOSAGE_ERR_INVALID_ARG;
     r.xcd_remap = s.xcd_remap ? 1 : 0;
     r.HW = 1;
 
@@ -449,8 +449,7 @@ extern "C" autosage_status_t autosage_baseline_schedule(autosage_schedule_t* out
 // ------------------------------------------------------------------------------------------
 static bool sizes_ok(int64_t n_rows, int64_t n_cols, int64_t nnz)
 {
-    return n_rows >= 0 && n_cols >= 0 && nnz >= 0 && nnz < (int64_t(1) << 31) && n_rows < (int64_t(1) << 31) - 1 &&
-           n_cols < (int64_t(1) << 31);
+    return n_rows >= 0 && n_cols >= 0 && nnz >= 0 && nnz <= kMaxNnz && n_rows <= kMaxNnz && n_cols < (int64_t(1) << 31);
 }
 
 extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
@@ -577,8 +576,8 @@ extern "C" autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64
     if (hub_t > 0 && hub_t < kMinHubT) return AUTOSAGE_ERR_INVALID_ARG;
     if (!rowptr || (nnz > 0 && (!in || !out))) return AUTOSAGE_ERR_INVALID_ARG;
     if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
-    const int chunk = hub_t > 0 ? (hub_chunk > 0 ? hub_chunk : hub_t) : 0;
-    if (hub_t > 0 && chunk < kMinHubT) return AUTOSAGE_ERR_INVALID_ARG;
+    const int chunk = effective_hub_chunk(hub_t, hub_chunk);
+    if (hub_t > 0 && (chunk < kMinHubT || chunk > kMaxHubChunk)) return AUTOSAGE_ERR_INVALID_ARG;
     SoftmaxArgs a{};
     a.rows = RowMap{0, 1, (int32_t)n_rows, 0};
     a.rowptr = rowptr;
@@ -764,8 +763,9 @@ extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autos
     int hub_t = kSelectorMinHubT, chunk = kSelectorMinChunk;
     if (sched) {
         hub_t = sched->hub_t;
-        chunk = sched->hub_t > 0 ? (sched->hub_chunk > 0 ? sched->hub_chunk : sched->hub_t) : 0;
-        if (hub_t < 0 || (hub_t > 0 && (hub_t < kMinHubT || chunk < kMinHubT))) return AUTOSAGE_ERR_INVALID_ARG;
+        chunk = effective_hub_chunk(sched->hub_t, sched->hub_chunk);
+        if (hub_t < 0 || (hub_t > 0 && (hub_t < kMinHubT || chunk < kMinHubT || chunk > kMaxHubChunk)))
+            return AUTOSAGE_ERR_INVALID_ARG;
     } else if (op == AUTOSAGE_OP_ATTENTION) {
         hub_t = chunk = 256;               // smallest threshold the attention selector proposes
     }
@@ -929,8 +929,8 @@ extern "C" autosage_status_t autosage_csr_row_softmax_backward(autosage_handle_t
     if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
     if (n_rows == 0 || nnz == 0) return AUTOSAGE_OK;
     if (!rowptr || !P || !dP || !dS) return AUTOSAGE_ERR_INVALID_ARG;
-    const int chunk = hub_t > 0 ? (hub_chunk > 0 ? hub_chunk : hub_t) : 0;
-    if (hub_t > 0 && chunk < kMinHubT) return AUTOSAGE_ERR_INVALID_ARG;
+    const int chunk = effective_hub_chunk(hub_t, hub_chunk);
+    if (hub_t > 0 && (chunk < kMinHubT || chunk > kMaxHubChunk)) return AUTOSAGE_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     SoftmaxBwdArgs a{};
     a.rows = RowMap{0, 1, (int32_t)n_rows, 0};

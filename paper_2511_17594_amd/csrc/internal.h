@@ -99,10 +99,23 @@ struct autosage_ctx {
 namespace autosage {
 
 constexpr int kMinHubT = 64;               // smallest split threshold the library accepts
+// The kernels hold nonzero positions and row numbers in int32 and step them by at most one chunk or one
+// workgroup's stride past the end of a row: both limits together keep every such sum below 2^31.
+constexpr int kMaxHubChunk = 1 << 20;                                  // longest chunk of a split row
+constexpr int64_t kMaxNnz = (int64_t(1) << 31) - (int64_t(1) << 20);   // most nonzeros, and most rows, of a call
 constexpr int kSelectorMinHubT = 512;      // smallest threshold the selector proposes for SpMM / SDDMM
 constexpr int kSelectorMinChunk = 256;     // shortest hub chunk the selector proposes
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Chunk length in force for a threshold: an explicit one as given, else the threshold itself (at most
+// kMaxHubChunk); 0 when rows are not split.
+inline int effective_hub_chunk(int hub_t, int hub_chunk)
+{
+    if (hub_t <= 0) return 0;
+    if (hub_chunk > 0) return hub_chunk;
+    return hub_t < kMaxHubChunk ? hub_t : kMaxHubChunk;
+}
 
 // Largest power of two <= 16 that divides the pointer value and ld * elem_size.
 int common_alignment(const void* p, int64_t ld, int elem_size);

@@ -70,7 +70,7 @@ __global__ void __launch_bounds__(kPartThreads) hub_count_kernel(PartDev a)
             const int deg = row_degree(a, idx);
             if (deg >= a.hub_t) {
                 ++nh;
-                nc += (deg + a.hub_chunk - 1) / a.hub_chunk;
+                nc += (deg - 1) / a.hub_chunk + 1;
             }
         }
     }
@@ -103,7 +103,7 @@ __global__ void __launch_bounds__(kPartThreads) hub_fill_kernel(PartDev a)
         deg[r] = idx < a.rows.count ? row_degree(a, idx) : -1;
         if (deg[r] >= a.hub_t) {
             ++nh;
-            nc += (deg[r] + a.hub_chunk - 1) / a.hub_chunk;
+            nc += (deg[r] - 1) / a.hub_chunk + 1;
         }
     }
     int tx, ty;
@@ -116,7 +116,7 @@ __global__ void __launch_bounds__(kPartThreads) hub_fill_kernel(PartDev a)
         if (deg[r] < 0) continue;
         if (deg[r] >= a.hub_t) {
             a.hub_rows[h] = idx;
-            c += (deg[r] + a.hub_chunk - 1) / a.hub_chunk;
+            c += (deg[r] - 1) / a.hub_chunk + 1;
             a.chunk_ptr[h + 1] = c;
             ++h;
         } else if (a.light_rows) {

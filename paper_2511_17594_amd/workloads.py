@@ -330,6 +330,34 @@ def hub_split_graph(n: int = 20000, n_hub: int = 32, hub_deg: int = 5000,
     return csr_from_degrees(rng, deg, n)
 
 
+def largest_input(nnz: int, n_rows: int = 1050000, n_cols: int = 1 << 20, hub_row: int = 7,
+                  hub_deg: int = 300000, seed: int = 0) -> CSR:
+    """A matrix with exactly `nnz` stored entries, for the size limit of the library (about 17 GB of host
+    memory at 2^31 - 2^20 entries).  Row i holds 2040 + i % 8 entries, row 5 none, row `hub_row` hub_deg, and
+    the last row whatever is left, so the last nonzero of the last (long) row sits at position nnz - 1.
+    Columns are uniform and unsorted, duplicates may occur (both are legal inputs); values U[-1, 1).
+    """
+    rng = rng_for(seed, 8)
+    deg = 2040 + (np.arange(n_rows, dtype=np.int64) % 8)
+    deg[5] = 0
+    deg[hub_row] = hub_deg
+    deg[-1] = 0
+    rest = int(nnz) - int(deg.sum())
+    if rest < 0:
+        raise ValueError("nnz too small for %d rows" % n_rows)
+    deg[-1] = rest
+    rowptr = np.zeros(n_rows + 1, dtype=np.int64)
+    np.cumsum(deg, out=rowptr[1:])
+    colind = np.empty(nnz, dtype=np.int32)
+    val = np.empty(nnz, dtype=np.float32)
+    step = 1 << 26
+    for lo in range(0, nnz, step):                       # in pieces: bounded temporaries
+        hi = min(nnz, lo + step)
+        colind[lo:hi] = rng.integers(0, n_cols, size=hi - lo, dtype=np.int32)
+        val[lo:hi] = rng.random(hi - lo, dtype=np.float32) * np.float32(2.0) - np.float32(1.0)
+    return CSR(n_rows, n_cols, rowptr.astype(np.int32), colind, val)
+
+
 # --------------------------------------------------------------------------- #
 # index-only helper used by tests that check sampled rows of a large result
 # --------------------------------------------------------------------------- #

@@ -177,3 +177,25 @@ def test_env_toggles_are_read_at_creation(ab, monkeypatch, tmp_path):
     h.cache_insert(7, 64, ab.OP_SPMM, ab.F32, ab.baseline_schedule())
     h.close()                                               # AUTOSAGE_CACHE is written on destroy
     assert os.path.exists(path) and "autosage-cache-v2" in open(path).read()
+
+
+def test_size_limits_are_checked_before_anything_else(ab, host):
+    """nnz and n_rows up to 2^31 - 2^20 pass the argument check (the host-only handle then refuses to compute);
+    one more is an invalid argument.  A hub chunk longer than 2^20 is refused, a threshold above it is not."""
+    header = open(os.path.join(ROOT, "include", "autosage.h")).read()
+    limit = int(re.search(r"#define AUTOSAGE_MAX_NNZ (\d+)LL", header).group(1))
+    assert limit == (1 << 31) - (1 << 20)
+    for nnz, status in ((limit, ab.ERR_UNSUPPORTED), (limit + 1, ab.ERR_INVALID_ARG)):
+        with pytest.raises(ab.AutosageError) as ei:
+            host.spmm(4, 4, None, None, None, None, None, 8, nnz=nnz, stream=0)
+        assert ei.value.status == status
+    with pytest.raises(ab.AutosageError) as ei:
+        host.spmm(limit + 1, 4, None, None, None, None, None, 8, nnz=0, stream=0)
+    assert ei.value.status == ab.ERR_INVALID_ARG
+    s = ab.Schedule(hub_t=1 << 21)
+    assert host.workspace_bytes(ab.OP_SPMM, 1000, 50000, 64, 1, s) >= 256
+    s.hub_chunk = (1 << 20) + 1
+    with pytest.raises(ab.AutosageError):
+        host.workspace_bytes(ab.OP_SPMM, 1000, 50000, 64, 1, s)
+    s.hub_chunk = 1 << 20
+    assert host.workspace_bytes(ab.OP_SPMM, 1000, 50000, 64, 1, s) >= 256
