@@ -16,7 +16,7 @@
  *     ordinary host memory.  The library never frees or keeps a caller pointer.
  *   - Indices are int32.  Dense operands are row-major with the feature index minor and a
  *     leading dimension (in elements) >= the feature count.
- *   - Dense INPUT operands have dtype `dt` (fp32 or bf16 bit patterns); val, scores and all
+ *   - Dense INPUT operands have dtype `dt` (fp32, bf16 or IEEE fp16 bit patterns); val, scores and all
  *     outputs are fp32; accumulation is fp32.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls with an
  *     explicit schedule only enqueue work and never synchronise.  Calls with sched == NULL
@@ -57,7 +57,7 @@ typedef enum {
     AUTOSAGE_ERR_REPLAY_MISS = 6
 } autosage_status_t;
 
-typedef enum { AUTOSAGE_F32 = 0, AUTOSAGE_BF16 = 1 } autosage_dtype_t;
+typedef enum { AUTOSAGE_F32 = 0, AUTOSAGE_BF16 = 1, AUTOSAGE_F16 = 2 } autosage_dtype_t;
 
 typedef enum {
     AUTOSAGE_OP_SPMM = 0,

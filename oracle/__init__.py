@@ -5,7 +5,8 @@ benchmark's CPU-baseline leg.  The GPU library and its Python binding never
 import this package, and this package never imports them.
 
 All functions take host NumPy arrays and return float64 / integer NumPy arrays.
-bf16 operands are passed as ``uint16`` bit patterns.
+bf16 operands are passed as ``uint16`` bit patterns, IEEE fp16 operands as ``numpy.float16`` arrays (widened
+to float32, which holds every fp16 value exactly, before the C code sees them).
 """
 from __future__ import annotations
 
@@ -57,7 +58,9 @@ def _dense(a):
         return a, F32
     if a.dtype == np.uint16:
         return a, BF16
-    raise TypeError("dense operands must be float32 or uint16 (bf16 bits), got %s" % a.dtype)
+    if a.dtype == np.float16:
+        return np.ascontiguousarray(a.astype(np.float32)), F32
+    raise TypeError("dense operands must be float32, float16 or uint16 (bf16 bits), got %s" % a.dtype)
 
 
 def num_threads() -> int:

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libautosage.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE_TOO_SMALL, ERR_HIP, ERR_IO, ERR_REPLAY_MISS = range(7)
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 OP_SPMM, OP_SDDMM, OP_SOFTMAX, OP_ATTENTION = 0, 1, 2, 3
 MAP_PLAIN, MAP_WAVE_ROW, MAP_MULTI_ROW, MAP_FUSED = 0, 1, 2, 3
 

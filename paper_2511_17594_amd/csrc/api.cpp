@@ -65,7 +65,7 @@ autosage_schedule_t baseline_schedule()
 autosage_status_t resolve_schedule(const autosage_schedule_t& s, int op, int32_t F, int dt, int heads,
                                    int align_in, int align_out, Resolved* out)
 {
-    const int esize = dt == DT_BF16 ? 2 : 4;
+    const int esize = dtype_bytes(dt);
     Resolved r{};
     if (F <= 0 || heads < 1) return AUTOSAGE_ERR_INVALID_ARG;
     if (s.mapping < AUTOSAGE_MAP_PLAIN || s.mapping > AUTOSAGE_MAP_MULTI_ROW) return AUTOSAGE_ERR_INVALID_ARG;
@@ -459,7 +459,7 @@ extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, 
                                            void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!h || !sizes_ok(n_rows, n_cols, nnz) || F <= 0 || ldb < F || ldc < F) return AUTOSAGE_ERR_INVALID_ARG;
-    if (dt != AUTOSAGE_F32 && dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (!dtype_known(dt)) return AUTOSAGE_ERR_INVALID_ARG;
     if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
     if (n_rows == 0) return AUTOSAGE_OK;
     if (!rowptr || !C || (nnz > 0 && (!colind || !val || !B))) return AUTOSAGE_ERR_INVALID_ARG;
@@ -471,7 +471,7 @@ extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, 
         if (s != AUTOSAGE_OK) return s;
         sched = &chosen;
     }
-    const int esize = dt == AUTOSAGE_BF16 ? 2 : 4;
+    const int esize = dtype_bytes(dt);
     Resolved r;
     autosage_status_t s = resolve_schedule(*sched, AUTOSAGE_OP_SPMM, F, dt, 1, common_alignment(B, ldb, esize),
                                            common_alignment(C, ldc, 4), &r);
@@ -505,7 +505,7 @@ extern "C" autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows,
 {
     (void)val;
     if (!h || !sizes_ok(n_rows, n_cols, nnz) || F <= 0 || ldx < F || ldy < F) return AUTOSAGE_ERR_INVALID_ARG;
-    if (dt != AUTOSAGE_F32 && dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (!dtype_known(dt)) return AUTOSAGE_ERR_INVALID_ARG;
     if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
     if (n_rows == 0 || nnz == 0) return AUTOSAGE_OK;
     if (!rowptr || !colind || !X || !Y || !out) return AUTOSAGE_ERR_INVALID_ARG;
@@ -517,7 +517,7 @@ extern "C" autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows,
         if (s != AUTOSAGE_OK) return s;
         sched = &chosen;
     }
-    const int esize = dt == AUTOSAGE_BF16 ? 2 : 4;
+    const int esize = dtype_bytes(dt);
     int al = common_alignment(X, ldx, esize);
     const int al2 = common_alignment(Y, ldy, esize);
     if (al2 < al) al = al2;
@@ -604,7 +604,7 @@ namespace autosage {
 
 autosage_status_t attention_alignment(const AttnCall& c)
 {
-    const int esize = c.dt == AUTOSAGE_BF16 ? 2 : 4;
+    const int esize = dtype_bytes(c.dt);
     const int64_t HD = (int64_t)c.H * c.d;
     // 16-byte lane loads are required: d must be a multiple of 16 / esize elements and the operands aligned
     if ((c.d * esize) % 16 != 0) return AUTOSAGE_ERR_UNSUPPORTED;
@@ -737,7 +737,7 @@ extern "C" autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t
 {
     (void)val;
     if (!h || !sizes_ok(N, N, nnz) || H <= 0 || d <= 0 || (int64_t)H * d >= (1 << 24)) return AUTOSAGE_ERR_INVALID_ARG;
-    if (in_dt != AUTOSAGE_F32 && in_dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (!dtype_known(in_dt)) return AUTOSAGE_ERR_INVALID_ARG;
     if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
     if (N == 0) return AUTOSAGE_OK;
     if (!rowptr || !O || (nnz > 0 && (!colind || !Q || !K || !V))) return AUTOSAGE_ERR_INVALID_ARG;
@@ -775,10 +775,10 @@ extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autos
         case AUTOSAGE_OP_SDDMM: b = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, 0); break;
         case AUTOSAGE_OP_SOFTMAX: b = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, 2 * (int64_t)H); break;
         case AUTOSAGE_OP_ATTENTION: {
-            // dtype is not an argument here: take the larger per-chunk state of the two element types
+            // dtype is not an argument here: take the largest per-chunk state over the element types
             AttnShape sh{};
             size_t fused_floats = 0;
-            for (int dt = 0; dt <= 1; ++dt)
+            for (int dt = DT_F32; dt <= DT_F16; ++dt)
                 if (attn_fused_shape(H, F, dt, &sh)) fused_floats = std::max(fused_floats, attn_fused_part_floats(sh));
             const size_t three = align_up(sizeof(float) * (size_t)nnz * H, 256) +
                                  hub_workspace_bytes(n_rows, nnz, hub_t, chunk, (int64_t)attention_part_floats(H, F));

@@ -5,6 +5,7 @@ namespace autosage {
 
 hipError_t attn_fused_f32(const AttnArgs&, const AttnShape&, int, const HubMeta*, float*, hipStream_t);
 hipError_t attn_fused_bf16(const AttnArgs&, const AttnShape&, int, const HubMeta*, float*, hipStream_t);
+hipError_t attn_fused_f16(const AttnArgs&, const AttnShape&, int, const HubMeta*, float*, hipStream_t);
 
 static int pow2_ceil_i(int x)
 {
@@ -15,7 +16,7 @@ static int pow2_ceil_i(int x)
 
 bool attn_fused_shape(int32_t H, int32_t d, int dt, AttnShape* s)
 {
-    const int vec = dt == DT_BF16 ? 8 : 4;
+    const int vec = 16 / dtype_bytes(dt);
     if (d % vec != 0) return false;
     const int lanes = d / vec;
     if (lanes > 64) return false;
@@ -36,12 +37,16 @@ size_t attn_fused_part_floats(const AttnShape& s) { return (size_t)s.KH * s.LH *
 
 hipError_t launch_attn_fused_rows(const AttnArgs& a, const AttnShape& s, hipStream_t stream)
 {
-    return a.dt == DT_BF16 ? attn_fused_bf16(a, s, 0, nullptr, nullptr, stream) : attn_fused_f32(a, s, 0, nullptr, nullptr, stream);
+    if (a.dt == DT_BF16) return attn_fused_bf16(a, s, 0, nullptr, nullptr, stream);
+    if (a.dt == DT_F16) return attn_fused_f16(a, s, 0, nullptr, nullptr, stream);
+    return attn_fused_f32(a, s, 0, nullptr, nullptr, stream);
 }
 
 hipError_t launch_attn_fused_hub(const AttnArgs& a, const AttnShape& s, const HubMeta& meta, float* part, hipStream_t stream)
 {
-    return a.dt == DT_BF16 ? attn_fused_bf16(a, s, 1, &meta, part, stream) : attn_fused_f32(a, s, 1, &meta, part, stream);
+    if (a.dt == DT_BF16) return attn_fused_bf16(a, s, 1, &meta, part, stream);
+    if (a.dt == DT_F16) return attn_fused_f16(a, s, 1, &meta, part, stream);
+    return attn_fused_f32(a, s, 1, &meta, part, stream);
 }
 
 }  // namespace autosage

@@ -10,7 +10,13 @@ constexpr int kWave = 64;
 
 struct bf16_t { uint16_t bits; };   // storage only; arithmetic is done in fp32
 
+struct f16_t { uint16_t bits; };    // IEEE binary16 storage; arithmetic is done in fp32
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t b)
+{
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(b)));     // exact
+}
 
 // Loads VEC consecutive elements of T starting at ptr (ptr is VEC*sizeof(T) aligned) as fp32.
 template <typename T, int VEC> struct VecIO;
@@ -51,6 +57,32 @@ template <> struct VecIO<bf16_t, 8> {
         v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
         v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xFFFF0000u);
         v[6] = __uint_as_float(t.w << 16); v[7] = __uint_as_float(t.w & 0xFFFF0000u);
+    }
+};
+
+template <> struct VecIO<f16_t, 1> {
+    static __device__ __forceinline__ void load(const f16_t* p, float* v) { v[0] = f16_bits_to_f32(p->bits); }
+};
+template <> struct VecIO<f16_t, 2> {
+    static __device__ __forceinline__ void load(const f16_t* p, float* v) {
+        uint32_t t = *reinterpret_cast<const uint32_t*>(p);
+        v[0] = f16_bits_to_f32(t & 0xFFFFu); v[1] = f16_bits_to_f32(t >> 16);
+    }
+};
+template <> struct VecIO<f16_t, 4> {
+    static __device__ __forceinline__ void load(const f16_t* p, float* v) {
+        uint2 t = *reinterpret_cast<const uint2*>(p);
+        v[0] = f16_bits_to_f32(t.x & 0xFFFFu); v[1] = f16_bits_to_f32(t.x >> 16);
+        v[2] = f16_bits_to_f32(t.y & 0xFFFFu); v[3] = f16_bits_to_f32(t.y >> 16);
+    }
+};
+template <> struct VecIO<f16_t, 8> {
+    static __device__ __forceinline__ void load(const f16_t* p, float* v) {
+        uint4 t = *reinterpret_cast<const uint4*>(p);
+        v[0] = f16_bits_to_f32(t.x & 0xFFFFu); v[1] = f16_bits_to_f32(t.x >> 16);
+        v[2] = f16_bits_to_f32(t.y & 0xFFFFu); v[3] = f16_bits_to_f32(t.y >> 16);
+        v[4] = f16_bits_to_f32(t.z & 0xFFFFu); v[5] = f16_bits_to_f32(t.z >> 16);
+        v[6] = f16_bits_to_f32(t.w & 0xFFFFu); v[7] = f16_bits_to_f32(t.w >> 16);
     }
 };
 

@@ -8,7 +8,9 @@
 namespace autosage {
 
 enum Mapping { MAP_PLAIN = 0, MAP_WAVE_ROW = 1, MAP_MULTI_ROW = 2 };
-enum DType { DT_F32 = 0, DT_BF16 = 1 };
+enum DType { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+inline bool dtype_known(int dt) { return dt == DT_F32 || dt == DT_BF16 || dt == DT_F16; }
+inline int dtype_bytes(int dt) { return dt == DT_F32 ? 4 : 2; }
 
 // The rows a launch covers, in blocks of 2^block_shift consecutive rows:
 //   row(idx) = first + (idx >> block_shift) * stride + (idx & (2^block_shift - 1)),  idx in [0, count).

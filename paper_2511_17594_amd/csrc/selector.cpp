@@ -159,7 +159,7 @@ void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, in
     (void)n_cols;
     Model m;
     if (h && h->cu_count > 0) m.waves = h->cu_count * 32;
-    const int esize = dt == DT_BF16 ? 2 : 4;
+    const int esize = dtype_bytes(dt);
     const Params dflt;
     const Params& p = h ? h->params : dflt;
     std::vector<std::pair<double, autosage_schedule_t>> all;
@@ -291,7 +291,7 @@ extern "C" autosage_status_t autosage_cache_load(autosage_handle_t h, const char
         char* end = nullptr;
         k.graph_sig = std::strtoull(sig_hex.c_str(), &end, 16);
         if (end == sig_hex.c_str() || *end != '\0') continue;
-        if (s.mapping < 0 || s.mapping > 3 || k.op < 0 || k.op > 3 || k.dt < 0 || k.dt > 1 || k.F <= 0 || k.H <= 0) continue;
+        if (s.mapping < 0 || s.mapping > 3 || k.op < 0 || k.op > 3 || !dtype_known(k.dt) || k.F <= 0 || k.H <= 0) continue;
         h->cache[k] = e;
     }
     return AUTOSAGE_OK;
@@ -358,7 +358,7 @@ struct OpInput {
 autosage_status_t run_once(autosage_ctx* h, const OpInput& in, const RowMap& rows, const autosage_schedule_t& s, void* ws, size_t ws_bytes,
                            hipStream_t st)
 {
-    const int esize = in.dt == DT_BF16 ? 2 : 4;
+    const int esize = dtype_bytes(in.dt);
     Resolved r;
     if (in.op == AUTOSAGE_OP_ATTENTION) {
         const AttnCall c{in.n_rows, in.nnz, in.rowptr, in.colind, in.d0, in.d1, in.d2, in.out, in.H, in.F, in.scale, in.dt};
@@ -455,7 +455,7 @@ std::string num(double x)
 static void shortlist_attention(const autosage_ctx* h, int64_t nnz, const int64_t* hist, int64_t max_deg, int32_t H,
                                 int32_t d, int dt, std::vector<autosage_schedule_t>* out, std::vector<double>* est)
 {
-    const int esize = dt == DT_BF16 ? 2 : 4;
+    const int esize = dtype_bytes(dt);
     AttnShape shape{};
     const bool can_fuse = attn_fused_shape(H, d, dt, &shape);
     const double row_bytes = 2.0 * H * d * esize;                  // one K row and one V row per nonzero
@@ -566,7 +566,7 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
     }
 
     // 3. shortlist
-    const int esize = dt == AUTOSAGE_BF16 ? 2 : 4;
+    const int esize = dtype_bytes(dt);
     int al = common_alignment(dense0, ld0, esize);
     if (op == AUTOSAGE_OP_SDDMM) al = std::min(al, common_alignment(dense1, ld1, esize));
     else if (op == AUTOSAGE_OP_SPMM) al = std::min(al, common_alignment(out, ld_out, 4));
@@ -666,7 +666,7 @@ extern "C" autosage_status_t autosage_decide(autosage_handle_t h, autosage_op_t 
 {
     if (!h || !chosen || !rowptr || F <= 0 || n_rows < 0 || nnz < 0) return AUTOSAGE_ERR_INVALID_ARG;
     if (op != AUTOSAGE_OP_SPMM && op != AUTOSAGE_OP_SDDMM) return AUTOSAGE_ERR_INVALID_ARG;
-    if (dt != AUTOSAGE_F32 && dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (!dtype_known(dt)) return AUTOSAGE_ERR_INVALID_ARG;
     if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
     if (nnz > 0 && (!colind || !dense0 || !out || (op == AUTOSAGE_OP_SPMM && !val) || (op == AUTOSAGE_OP_SDDMM && !dense1)))
         return AUTOSAGE_ERR_INVALID_ARG;
@@ -682,7 +682,7 @@ extern "C" autosage_status_t autosage_decide_attention(autosage_handle_t h, int6
                                                        autosage_schedule_t* chosen)
 {
     if (!h || !chosen || !rowptr || H <= 0 || d <= 0 || N < 0 || nnz < 0) return AUTOSAGE_ERR_INVALID_ARG;
-    if (dt != AUTOSAGE_F32 && dt != AUTOSAGE_BF16) return AUTOSAGE_ERR_INVALID_ARG;
+    if (!dtype_known(dt)) return AUTOSAGE_ERR_INVALID_ARG;
     if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
     if (!O || (nnz > 0 && (!colind || !Q || !K || !V))) return AUTOSAGE_ERR_INVALID_ARG;
     const AttnCall c{N, nnz, rowptr, colind, Q, K, V, O, H, d, scale, (int)dt};

@@ -5,8 +5,10 @@ namespace autosage {
 
 hipError_t spmm_rows_f32(const SpmmArgs&, const Resolved&, hipStream_t);
 hipError_t spmm_rows_bf16(const SpmmArgs&, const Resolved&, hipStream_t);
+hipError_t spmm_rows_f16(const SpmmArgs&, const Resolved&, hipStream_t);
 hipError_t spmm_hub_partial_f32(const SpmmArgs&, const Resolved&, const HubMeta&, float*, hipStream_t);
 hipError_t spmm_hub_partial_bf16(const SpmmArgs&, const Resolved&, const HubMeta&, float*, hipStream_t);
+hipError_t spmm_hub_partial_f16(const SpmmArgs&, const Resolved&, const HubMeta&, float*, hipStream_t);
 
 // Adds the partial rows of a hub row's chunks in ascending chunk order (fixed order -> reproducible).
 __global__ void __launch_bounds__(256) spmm_hub_combine_kernel(SpmmDev a)
@@ -25,14 +27,17 @@ __global__ void __launch_bounds__(256) spmm_hub_combine_kernel(SpmmDev a)
 
 hipError_t launch_spmm_rows(const SpmmArgs& a, const Resolved& r, hipStream_t stream)
 {
-    return a.dt == DT_BF16 ? spmm_rows_bf16(a, r, stream) : spmm_rows_f32(a, r, stream);
+    if (a.dt == DT_BF16) return spmm_rows_bf16(a, r, stream);
+    if (a.dt == DT_F16) return spmm_rows_f16(a, r, stream);
+    return spmm_rows_f32(a, r, stream);
 }
 
 hipError_t launch_spmm_hub(const SpmmArgs& a, const Resolved& r, const HubMeta& meta, float* part, hipStream_t stream)
 {
     if (meta.cap_hub == 0 || meta.cap_chunks == 0) return hipSuccess;
-    hipError_t e = a.dt == DT_BF16 ? spmm_hub_partial_bf16(a, r, meta, part, stream)
-                                   : spmm_hub_partial_f32(a, r, meta, part, stream);
+    hipError_t e = a.dt == DT_BF16  ? spmm_hub_partial_bf16(a, r, meta, part, stream)
+                   : a.dt == DT_F16 ? spmm_hub_partial_f16(a, r, meta, part, stream)
+                                    : spmm_hub_partial_f32(a, r, meta, part, stream);
     if (e != hipSuccess) return e;
     SpmmDev d{};
     d.rows = a.rows;

@@ -48,7 +48,7 @@ def main(argv=None):
     ap.add_argument("--widths", default=None)
     ap.add_argument("--ops", default="spmm,sddmm")
     ap.add_argument("--ablate", default="alpha,vec,hubt,probe")
-    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16", "f16"])
     ap.add_argument("--iters", type=int, default=10)
     args = ap.parse_args(argv)
 
@@ -80,7 +80,7 @@ def main(argv=None):
     h_replay = ab.Handle(0)          # sees one default-parameter decision per (op, F): its cache is the one saved
     meta["device_sig"] = None
     base = ab.baseline_schedule()
-    dt = ab.BF16 if args.dtype == "bf16" else ab.F32
+    dt = {"f32": ab.F32, "bf16": ab.BF16, "f16": ab.F16}[args.dtype]
     decisions = open(os.path.join(args.out, "%s_decisions.jsonl" % args.workload), "w")
 
     def timed(fn, iters):
@@ -120,8 +120,9 @@ def main(argv=None):
         g = torch.Generator(device="cuda").manual_seed(F)
         B = torch.randn((M, F), device="cuda", generator=g)
         X = torch.randn((N, F), device="cuda", generator=g)
-        if args.dtype == "bf16":
-            B, X = B.to(torch.bfloat16), X.to(torch.bfloat16)
+        if args.dtype != "f32":
+            half = torch.bfloat16 if args.dtype == "bf16" else torch.float16
+            B, X = B.to(half), X.to(half)
         C = torch.empty((N, F), device="cuda")
         out = torch.empty(max(nnz, 1), device="cuda")
         box = {"ws": torch.empty(h.workspace_bytes(ab.OP_SPMM, N, nnz, F), dtype=torch.uint8, device="cuda")}
@@ -163,7 +164,7 @@ def main(argv=None):
 
             if "vec" in which and choice["mapping"] != base.mapping:
                 # Vector loads against 4-byte (fp32) / 2-byte (bf16) scalar loads, everything else as chosen.
-                scalar = 2 if args.dtype == "bf16" else 4
+                scalar = 4 if args.dtype == "f32" else 2
                 t_on = timed(lambda: fn(sched_from(choice)), args.iters)
                 t_off, off_map = None, None
                 # the multi-row mapping has no scalar form at widths of a whole wavefront: use wave-per-row there

@@ -4,7 +4,7 @@
 
 For every width: the selector's choice (cold call, then steady state from its cache), time (median of
 `--iters` HIP-event timings), GFLOP/s = 2*nnz*F/t, algorithmic GB/s (every gathered dense row counted
-once per nonzero; `--dtype bf16` halves the bytes of a gathered row) and its fraction of the 8 TB/s HBM peak, and the guardrail's fallback kernel on the
+once per nonzero; `--dtype bf16` / `f16` halve the bytes of a gathered row) and its fraction of the 8 TB/s HBM peak, and the guardrail's fallback kernel on the
 same input.  `--vendor` adds the vendor SpMM reached through torch.sparse.mm.  Workloads: config1..4
 (the benchmark configurations), er (Erdos-Renyi N = 200000, p = 2e-5, the shape of the paper's
 extreme-sparsity stressor) and hubsplit_5k / hubsplit_12k (N = 20000, a few rows of degree 5000 /
@@ -53,7 +53,7 @@ def main(argv=None):
     ap.add_argument("--iters", type=int, default=10)
     ap.add_argument("--vendor", action="store_true")
     ap.add_argument("--no-sddmm", action="store_true")
-    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="element type of the dense input operands")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16", "f16"], help="element type of the dense input operands")
     args = ap.parse_args(argv)
 
     import torch
@@ -96,13 +96,14 @@ def main(argv=None):
         g = torch.Generator(device="cuda").manual_seed(F)
         B = torch.randn((M, F), device="cuda", generator=g)
         X = torch.randn((N, F), device="cuda", generator=g)
-        if args.dtype == "bf16":
-            B, X = B.to(torch.bfloat16), X.to(torch.bfloat16)
+        if args.dtype != "f32":
+            half = torch.bfloat16 if args.dtype == "bf16" else torch.float16
+            B, X = B.to(half), X.to(half)
         C = torch.empty((N, F), device="cuda")
         out = torch.empty(max(nnz, 1), device="cuda")
         ws = torch.empty(h.workspace_bytes(ab.OP_SPMM, N, nnz, F), dtype=torch.uint8, device="cuda")
-        esz = 2 if args.dtype == "bf16" else 4
-        dt = ab.BF16 if args.dtype == "bf16" else ab.F32
+        esz = 4 if args.dtype == "f32" else 2
+        dt = {"f32": ab.F32, "bf16": ab.BF16, "f16": ab.F16}[args.dtype]
         bg = 4 * (N + 1) + 8 * nnz + nnz * F * esz + N * F * 4
         ops = [("SpMM", lambda s: h.spmm(N, M, rp, ci, va, B, C, F, dt=dt, sched=s, workspace=ws, stream=stream))]
         if not args.no_sddmm:

@@ -44,7 +44,9 @@ def _dt(t: torch.Tensor) -> int:
         return ab.F32
     if t.dtype == torch.bfloat16:
         return ab.BF16
-    raise TypeError("dense operands must be float32 or bfloat16, got %s" % t.dtype)
+    if t.dtype == torch.float16:
+        return ab.F16
+    raise TypeError("dense operands must be float32, bfloat16 or float16, got %s" % t.dtype)
 
 
 def _check_csr(rowptr, colind):

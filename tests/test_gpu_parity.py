@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 from paper_2511_17594_amd import workloads as W
-from util import dev, rel_l1_rows, rel_l1_segments
+from util import dev, dtype_code, rel_l1_rows, rel_l1_segments
 
 pytestmark = pytest.mark.gpu
 
@@ -61,7 +61,7 @@ def workspace(torch, handle, ab, op, A, F, H=1, sched=None):
 
 def run_spmm(torch, handle, ab, A, B, sched, dt=None):
     F = B.shape[1]
-    dt = ab.BF16 if B.dtype == np.uint16 else ab.F32
+    dt = dtype_code(ab, B)
     d_rp, d_ci, d_v, d_B = dev(A.rowptr, torch), dev(A.colind, torch), dev(A.val, torch), dev(B, torch)
     C = torch.full((A.n_rows, F), float("nan"), dtype=torch.float32, device="cuda")
     ws = workspace(torch, handle, ab, ab.OP_SPMM, A, F, 1, sched)
@@ -72,7 +72,7 @@ def run_spmm(torch, handle, ab, A, B, sched, dt=None):
 
 def run_sddmm(torch, handle, ab, A, X, Y, sched):
     F = X.shape[1]
-    dt = ab.BF16 if X.dtype == np.uint16 else ab.F32
+    dt = dtype_code(ab, X)
     d_rp, d_ci = dev(A.rowptr, torch), dev(A.colind, torch)
     out = torch.full((max(A.nnz, 1),), float("nan"), dtype=torch.float32, device="cuda")
     ws = workspace(torch, handle, ab, ab.OP_SDDMM, A, F, 1, sched)
@@ -142,15 +142,22 @@ def test_sddmm_f32_schedules(torch, handle, ab, skew_graph, F):
     assert ran >= 5
 
 
+@pytest.mark.parametrize("half", ["bf16", "f16"])
 @pytest.mark.parametrize("F", [8, 30, 64, 128, 520])
-def test_spmm_sddmm_bf16_operands(torch, handle, ab, skew_graph, F):
+def test_spmm_sddmm_bf16_operands(torch, handle, ab, skew_graph, F, half):
     A = skew_graph
     rng = np.random.default_rng(2000 + F)
-    B = W.float_to_bf16_bits(rng.standard_normal((A.n_cols, F)).astype(np.float32)).reshape(A.n_cols, F)
-    X = W.float_to_bf16_bits(rng.standard_normal((A.n_rows, F)).astype(np.float32)).reshape(A.n_rows, F)
+    B32 = rng.standard_normal((A.n_cols, F)).astype(np.float32)
+    X32 = rng.standard_normal((A.n_rows, F)).astype(np.float32)
+    if half == "bf16":
+        B = W.float_to_bf16_bits(B32).reshape(A.n_cols, F)
+        X = W.float_to_bf16_bits(X32).reshape(A.n_rows, F)
+        absb = lambda t: (t & np.uint16(0x7FFF))                  # |x| of a bf16 bit pattern
+    else:
+        B, X, absb = B32.astype(np.float16), X32.astype(np.float16), np.abs
+        B[3, 0], B[4, 0], X[2, 0] = np.float16(6.0e-8), np.float16(65504.0), np.float16(-6.1e-5)   # subnormal, largest
     ref_c = oracle.spmm(A.rowptr, A.colind, A.val, B)
     ref_s = oracle.sddmm(A.rowptr, A.colind, X, B)
-    absb = lambda t: (t & np.uint16(0x7FFF))                      # |x| of a bf16 bit pattern
     abs_c = oracle.spmm(A.rowptr, A.colind, np.abs(A.val), absb(B))
     abs_s = oracle.sddmm(A.rowptr, A.colind, absb(X), absb(B))
     for kw in (dict(mapping=0), dict(mapping=1), dict(mapping=1, hub_t=256, vec_bytes=4), dict(mapping=2, hub_t=512)):
@@ -161,7 +168,7 @@ def test_spmm_sddmm_bf16_operands(torch, handle, ab, skew_graph, F):
         except ab.AutosageError as e:
             assert e.status == ab.ERR_UNSUPPORTED and kw.get("mapping") == 2, (kw, str(e))
             continue
-        # the bf16 inputs are exact in both paths, so only fp32 accumulation differs
+        # the 16-bit inputs are exact in both paths, so only fp32 accumulation differs
         assert rel_l1_rows(C, ref_c, abs_c).max() <= TOL_F32, kw
         assert rel_l1_segments(out, ref_s, A.rowptr, abs_s).max() <= TOL_F32, kw
 
@@ -193,6 +200,7 @@ def test_row_softmax(torch, handle, ab, skew_graph, H, hub_t):
 @pytest.mark.parametrize("H,d,dtype,qk_std,hub_t", [
     (8, 64, "bf16", None, 256), (8, 64, "bf16", 1.0, 0), (2, 32, "bf16", 1.0, 128), (1, 128, "bf16", 1.0, 64),
     (3, 16, "bf16", 2.0, 512), (4, 16, "f32", 1.0, 256), (8, 64, "f32", 1.0, 0), (16, 8, "bf16", 1.0, 256),
+    (8, 64, "f16", 1.0, 256), (2, 32, "f16", 2.0, 0),
 ])
 def test_csr_attention(torch, handle, ab, skew_graph, H, d, dtype, qk_std, hub_t):
     A = skew_graph
@@ -201,6 +209,9 @@ def test_csr_attention(torch, handle, ab, skew_graph, H, d, dtype, qk_std, hub_t
         Q, K, V = (W.bf16_bits_to_float(t).reshape(A.n_rows, H, d) * np.float32(1.001) for t in (Qb, Kb, Vb))
         Q, K, V = (np.ascontiguousarray(t, dtype=np.float32) for t in (Q, K, V))
         tol, dt = TOL_F32 * 4, ab.F32         # three fp32 stages stacked on each other
+    elif dtype == "f16":
+        Q, K, V = (W.bf16_bits_to_float(t).reshape(A.n_rows, H, d).astype(np.float16) for t in (Qb, Kb, Vb))
+        tol, dt = TOL_BF16, ab.F16
     else:
         Q, K, V, tol, dt = Qb, Kb, Vb, TOL_BF16, ab.BF16
     scale = float(d) ** -0.5
@@ -219,7 +230,7 @@ def test_csr_attention(torch, handle, ab, skew_graph, H, d, dtype, qk_std, hub_t
         assert err.max() <= tol, (mapping, H, d, dtype, float(err.max()), int(err.argmax()))
         assert np.all(got[A.degrees == 0] == 0.0), mapping
         # the bf16 path is in fact far inside its tolerance: inputs are exact, only fp32 rounding differs
-        if dtype == "bf16":
+        if dtype != "f32":
             assert err.max() <= 1e-4, mapping
 
 
@@ -337,3 +348,22 @@ def test_fixed_schedule_is_bit_reproducible(torch, handle, ab, skew_graph):
     C1 = run_spmm(torch, handle, ab, A, B, s)
     C2 = run_spmm(torch, handle, ab, A, B, s)
     assert np.array_equal(C1, C2)
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "f16"])
+def test_16_bit_operands_are_decoded_exactly(torch, handle, ab, fmt):
+    """Identity pattern with unit values: C must equal the 16-bit operand's values bit for bit (the tables hold
+    what the two formats define, subnormals and the largest finite value included)."""
+    import os
+    golden = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "%s_values.txt" % fmt)
+    rows = [l.split() for l in open(golden) if l.strip() and not l.startswith("#")]
+    bits = np.array([int(b, 16) for b, _ in rows], dtype=np.uint16)
+    vals = np.array([float(v) for _, v in rows], dtype=np.float32)
+    n = bits.size
+    A = W.CSR(n, n, np.arange(n + 1, dtype=np.int32), np.arange(n, dtype=np.int32), np.ones(n, np.float32))
+    for F, kw in ((8, dict(mapping=1, vec_bytes=16)), (8, dict(mapping=2)), (4, dict(mapping=1, vec_bytes=8)),
+                  (6, dict(mapping=1, vec_bytes=4)), (3, dict(mapping=1, vec_bytes=2)), (5, dict(mapping=0))):
+        B = np.repeat(bits[:, None], F, axis=1)
+        B = B if fmt == "bf16" else B.view(np.float16)
+        C = run_spmm(torch, handle, ab, A, np.ascontiguousarray(B), sched_of(ab, **kw))
+        assert np.array_equal(C, np.repeat(vals[:, None], F, axis=1)), (fmt, F, kw)

@@ -115,6 +115,26 @@ def test_spmm_bf16_operand_values():
     assert W.float_to_bf16_bits(np.array([1.0 + 3 * 2.0 ** -8], np.float32))[0] == 0x3F82
 
 
+def test_spmm_fp16_operand_values():
+    """IEEE binary16 operands: the table holds the values the format's definition gives for each pattern."""
+    bits, vals = [], []
+    for line in open(os.path.join(GOLDEN, "f16_values.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        b, v = line.split()
+        bits.append(int(b, 16))
+        vals.append(float(v))
+    n = len(bits)
+    for u, v in zip(bits, vals):                       # the definition, written out
+        sgn, e, f = (-1.0 if u >> 15 else 1.0), (u >> 10) & 31, u & 1023
+        assert v == sgn * (2.0 ** (e - 15) * (1 + f / 1024) if e else 2.0 ** -14 * f / 1024)
+    Bh = np.array(bits, dtype=np.uint16).view(np.float16).reshape(n, 1)
+    C = oracle.spmm(np.arange(n + 1, dtype=np.int32), np.arange(n, dtype=np.int32), np.ones(n, np.float32), Bh)
+    assert np.array_equal(C[:, 0], np.array(vals))
+    out = oracle.sddmm(np.arange(n + 1, dtype=np.int32), np.arange(n, dtype=np.int32), Bh, np.ones((n, 1), np.float16))
+    assert np.array_equal(out, np.array(vals))
+
+
 # ----------------------------------------------------------------- SDDMM ---
 @pytest.mark.parametrize("n_rows,n_cols,F", [(23, 23, 6), (31, 17, 9)])
 def test_sddmm_equals_masked_dense_product(n_rows, n_cols, F):

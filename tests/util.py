@@ -11,6 +11,11 @@ def dev(a, torch, dtype=None):
     return t.cuda() if dtype is None else t.to(dtype).cuda()
 
 
+def dtype_code(ab, a):
+    """Library dtype of a host dense operand: uint16 = bf16 bit patterns, float16 = IEEE fp16, else fp32."""
+    return ab.BF16 if a.dtype == np.uint16 else ab.F16 if a.dtype == np.float16 else ab.F32
+
+
 CANCEL_FLOOR = 0.1   # a row whose result cancels below 10 % of the magnitude of its terms is scaled by that floor
 
 
