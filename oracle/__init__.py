@@ -198,3 +198,23 @@ def row_softmax_backward(rowptr, P, dP) -> np.ndarray:
                                          _p(dS))
     assert rc == 0
     return dS
+
+
+def csr_attention_backward(rowptr, colind, Q, K, V, dO, scale):
+    """(dQ, dK, dV) of csr_attention for the upstream gradient dO [N, H, d]; float64 arrays [N, H, d]."""
+    lib = _load()
+    rowptr, colind = _i32(rowptr), _i32(colind)
+    Q, dt = _dense(Q)
+    K, dt2 = _dense(K)
+    V, dt3 = _dense(V)
+    assert dt == dt2 == dt3 and Q.ndim == 3 and Q.shape == K.shape == V.shape
+    N, H, d = Q.shape
+    dO = np.ascontiguousarray(dO, dtype=np.float64)
+    assert dO.shape == (N, H, d) and rowptr.shape[0] == N + 1
+    assert colind.size == 0 or int(colind.max()) < N
+    dQ, dK, dV = (np.zeros((N, H, d), dtype=np.float64) for _ in range(3))
+    rc = lib.oracle_csr_attention_backward(ctypes.c_int64(N), _p(rowptr), _p(colind), _p(Q), _p(K), _p(V), _p(dO),
+                                           ctypes.c_int32(H), ctypes.c_int32(d), ctypes.c_double(scale), ctypes.c_int(dt),
+                                           _p(dQ), _p(dK), _p(dV))
+    assert rc == 0
+    return dQ, dK, dV

@@ -20,10 +20,11 @@
  *   oracle_hub_partition Kernel-variant table: heavy rows (degree >= hubT) vs others;
  *                        the chunking of heavy rows is this project's own scheme.
  *   oracle_decide        Scheduler subsection + decision sketch + Proposition 1.
- *   oracle_csr_transpose, oracle_row_softmax_backward
+ *   oracle_csr_transpose, oracle_row_softmax_backward, oracle_csr_attention_backward
  *                        the adjoints needed when the operators sit in a training step (Introduction:
  *                        training throughput is bounded by these aggregations): d/dB of C = A B is A^T dC,
- *                        and the Jacobian-transpose product of the row-softmax.
+ *                        the Jacobian-transpose product of the row-softmax, and the chain rule through the
+ *                        three steps of the attention pipeline.
  *
  * All pins for these functions live in tests/test_oracle_*.py.
  */
@@ -293,5 +294,63 @@ int oracle_row_softmax_backward(int64_t n_rows, const int32_t* rowptr, const dou
             for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) dS[p * H + h] = P[p * H + h] * (dP[p * H + h] - dot);
         }
     }
+    return 0;
+}
+
+/* Adjoint of oracle_csr_attention: given dO = dL/dO ([N, H, d] doubles) it returns dL/dQ, dL/dK, dL/dV
+ * ([N, H, d] doubles) by the chain rule through the three steps, in reverse:
+ *   O = P V        ->  dV[j,h,:] += P[p,h] * dO[i,h,:],   dP[p,h] = <dO[i,h,:], V[j,h,:]>
+ *   P = softmax(S) ->  dS = oracle_row_softmax_backward(P, dP)
+ *   S = scale Q K^T on the pattern
+ *                  ->  dQ[i,h,:] += scale * dS[p,h] * K[j,h,:],   dK[j,h,:] += scale * dS[p,h] * Q[i,h,:]
+ * for every stored p = (i, j).  The scatter into rows j of dK and dV runs serially in storage order. */
+int oracle_csr_attention_backward(int64_t N, const int32_t* rowptr, const int32_t* colind,
+                                  const void* Q, const void* K, const void* V, const double* dO,
+                                  int32_t H, int32_t d, double scale, int dtype,
+                                  double* dQ, double* dK, double* dV)
+{
+    int64_t nnz = rowptr[N];
+    size_t cells = (size_t)(nnz > 0 ? nnz : 1) * H;
+    double* P = (double*)malloc(sizeof(double) * cells);
+    double* dP = (double*)malloc(sizeof(double) * cells);
+    double* dS = (double*)malloc(sizeof(double) * cells);
+    double* O = (double*)malloc(sizeof(double) * (size_t)(N > 0 ? N : 1) * H * d);
+    if (!P || !dP || !dS || !O) return 1;
+    double* S = (double*)malloc(sizeof(double) * cells);
+    if (!S) return 1;
+    oracle_csr_attention(N, rowptr, colind, Q, K, V, H, d, scale, dtype, S, P, O);
+    for (int64_t e = 0; e < N * H * d; ++e) dQ[e] = dK[e] = dV[e] = 0.0;
+    for (int64_t i = 0; i < N; ++i) {
+        for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+            int64_t j = colind[p];
+            for (int32_t h = 0; h < H; ++h) {
+                double acc = 0.0;
+                for (int32_t k = 0; k < d; ++k) {
+                    double g = dO[(i * H + h) * d + k];
+                    acc += g * load_as_double(V, (j * H + h) * d + k, dtype);
+                    dV[(j * H + h) * d + k] += P[p * H + h] * g;
+                }
+                dP[p * H + h] = acc;
+            }
+        }
+    }
+    oracle_row_softmax_backward(N, rowptr, P, dP, H, dS);
+    for (int64_t i = 0; i < N; ++i) {
+        for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+            int64_t j = colind[p];
+            for (int32_t h = 0; h < H; ++h) {
+                double w = scale * dS[p * H + h];
+                for (int32_t k = 0; k < d; ++k) {
+                    dQ[(i * H + h) * d + k] += w * load_as_double(K, (j * H + h) * d + k, dtype);
+                    dK[(j * H + h) * d + k] += w * load_as_double(Q, (i * H + h) * d + k, dtype);
+                }
+            }
+        }
+    }
+    free(S);
+    free(P);
+    free(dP);
+    free(dS);
+    free(O);
     return 0;
 }

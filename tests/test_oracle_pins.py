@@ -429,3 +429,50 @@ def test_softmax_backward_matches_autograd_and_finite_differences():
     # each row's gradient sums to zero (softmax is shift invariant)
     sums = np.add.reduceat(dS, A.rowptr[:-1][A.degrees > 0], axis=0)
     np.testing.assert_allclose(sums, 0.0, atol=1e-14)
+
+
+def test_attention_backward_matches_autograd_of_dense_attention_and_finite_differences():
+    """The three gradients against float64 autograd of the textbook masked dense attention, a central finite
+    difference through the oracle's own forward, and two structural facts (a column nobody attends to gets no
+    gradient; the identity pattern has P = 1, so dV = dO and dQ = dK = 0)."""
+    torch = pytest.importorskip("torch")
+    n, H, d, scale = 19, 3, 5, 0.4
+    A, rng = tiny_csr(n, n, 4.0, seed=47)
+    # make column 4 unused so that its K / V rows must receive exactly zero
+    cols = [[int(c) for c in A.colind[A.rowptr[i]:A.rowptr[i + 1]] if c != 4] for i in range(n)]
+    rowptr = np.concatenate([[0], np.cumsum([len(c) for c in cols])]).astype(np.int32)
+    colind = np.array([c for row in cols for c in row], dtype=np.int32)
+    Q, K, V = (rng.standard_normal((n, H, d)).astype(np.float32) for _ in range(3))
+    dO = rng.standard_normal((n, H, d))
+    dQ, dK, dV = oracle.csr_attention_backward(rowptr, colind, Q, K, V, dO, scale)
+
+    tq, tk, tv = (torch.tensor(t, dtype=torch.float64, requires_grad=True) for t in (Q, K, V))
+    mask = torch.zeros((n, n), dtype=torch.bool)
+    rows = np.repeat(np.arange(n), np.diff(rowptr))
+    mask[torch.from_numpy(rows), torch.from_numpy(colind.astype(np.int64))] = True
+    S = scale * torch.einsum("ihk,jhk->hij", tq, tk)
+    P = torch.nan_to_num(torch.softmax(S.masked_fill(~mask[None], float("-inf")), dim=2), nan=0.0)
+    O = torch.einsum("hij,jhk->ihk", P, tv)
+    (O * torch.tensor(dO)).sum().backward()
+    np.testing.assert_allclose(dQ, tq.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dK, tk.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dV, tv.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.all(dK[4] == 0.0) and np.all(dV[4] == 0.0)
+    empty = np.diff(rowptr) == 0
+    assert empty.any() and np.all(dQ[empty] == 0.0)
+
+    def loss(q, k, v):
+        return float((oracle.csr_attention(rowptr, colind, q, k, v, scale) * dO).sum())
+
+    for which, grad in ((0, dQ), (1, dK), (2, dV)):
+        i, h, c = 6, 1, 2
+        ops_p, ops_m = [Q.copy(), K.copy(), V.copy()], [Q.copy(), K.copy(), V.copy()]
+        base = float(ops_p[which][i, h, c])
+        hi, lo = np.float32(base + 2.0 ** -7), np.float32(base - 2.0 ** -7)        # exactly representable steps
+        ops_p[which][i, h, c], ops_m[which][i, h, c] = hi, lo
+        fd = (loss(*ops_p) - loss(*ops_m)) / (float(hi) - float(lo))
+        assert abs(fd - grad[i, h, c]) <= 2e-4 * max(1.0, abs(grad[i, h, c])), (which, fd, grad[i, h, c])
+
+    eye_ptr, eye_col = np.arange(n + 1, dtype=np.int32), np.arange(n, dtype=np.int32)
+    gq, gk, gv = oracle.csr_attention_backward(eye_ptr, eye_col, Q, K, V, dO, scale)
+    assert np.array_equal(gv, dO) and np.all(gq == 0.0) and np.all(gk == 0.0)
