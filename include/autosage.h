@@ -292,6 +292,31 @@ autosage_status_t autosage_csr_transpose(autosage_handle_t h, int64_t n_rows, in
 autosage_status_t autosage_gather_values(autosage_handle_t h, int64_t n, int32_t width, const int32_t* perm,
                                          const float* in, float* out, void* stream);
 
+/* Adjoint of autosage_csr_attention (training step around the attention pipeline of the Preliminaries:
+ * the chain rule through SpMM, row-softmax and SDDMM, all heads at once).  Given dO = dL/dO it writes
+ *   dV[j,h,:] = sum_p P[p,h] dO[i,h,:],   dP[p,h] = <dO[i,h,:], V[j,h,:]>,   dS = softmax'(P, dP),
+ *   dQ[i,h,:] = scale sum_p dS[p,h] K[j,h,:],   dK[j,h,:] = scale sum_p dS[p,h] Q[i,h,:]
+ * over the stored p = (i, j); the probabilities P are recomputed from Q and K, not stored by the forward.
+ * Q, K, V: [N, H, d] of in_dt (dev); dO, dQ, dK, dV: [N, H, d] fp32 (dev), none aliasing another.
+ * (t_rowptr, t_colind, perm) is the transposed pattern as autosage_csr_transpose returns it for the
+ * N x N pattern (computed once per graph by the caller).  hub_t / hub_chunk: rows of the pattern and of
+ * its transpose with at least hub_t entries are split into chunks (0 = no split).  Shapes as the forward:
+ * d * sizeof(in_dt) a multiple of 16, d a multiple of 4, 16-byte aligned tensors, else UNSUPPORTED.
+ * Rows without entries get zero gradients.  Deterministic: no atomics, fixed summation orders.
+ * Workspace from autosage_csr_attention_backward_workspace_bytes (3 * nnz * H floats + hub scratch). */
+autosage_status_t autosage_csr_attention_backward_workspace_bytes(autosage_handle_t h, int64_t N, int64_t nnz,
+                                                                  int32_t H, int32_t d, int32_t hub_t,
+                                                                  int32_t hub_chunk, size_t* bytes);
+autosage_status_t autosage_csr_attention_backward(autosage_handle_t h, int64_t N, int64_t nnz,
+                                                  const int32_t* rowptr, const int32_t* colind,
+                                                  const int32_t* t_rowptr, const int32_t* t_colind,
+                                                  const int32_t* perm,
+                                                  const void* Q, const void* K, const void* V, const float* dO,
+                                                  float* dQ, float* dK, float* dV,
+                                                  int32_t H, int32_t d, float scale, autosage_dtype_t in_dt,
+                                                  int32_t hub_t, int32_t hub_chunk,
+                                                  void* workspace, size_t workspace_bytes, void* stream);
+
 /* Telemetry (Contributions: deployment toggles and telemetry).  Between profile_begin and
  * profile_read every kernel stage the handle launches is bracketed by a pair of HIP events on its
  * stream.  profile_read waits for the recorded stages, writes JSON {"stage":{"calls":n,"total_ms":t},...}

@@ -77,6 +77,9 @@ def _load():
         "autosage_csr_transpose_workspace_bytes": [vp, i64, i64, i64, c.POINTER(sz)],
         "autosage_csr_transpose": [vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp],
         "autosage_gather_values": [vp, i64, i32, vp, vp, vp, vp],
+        "autosage_csr_attention_backward_workspace_bytes": [vp, i64, i64, i32, i32, i32, i32, c.POINTER(sz)],
+        "autosage_csr_attention_backward": [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
+                                            c.c_float, c.c_int, i32, i32, vp, sz, vp],
         "autosage_profile_begin": [vp],
         "autosage_profile_read": [vp, c.c_char_p, sz],
     }
@@ -225,6 +228,21 @@ class Handle:
                "autosage_gather_values")
 
     # -- metadata ----------------------------------------------------------------------
+    def csr_attention_backward_workspace_bytes(self, N, nnz, H, d, hub_t=0, hub_chunk=0) -> int:
+        out = ctypes.c_size_t()
+        _check(_lib.autosage_csr_attention_backward_workspace_bytes(self._h, N, nnz, H, d, hub_t, hub_chunk, ctypes.byref(out)),
+               "autosage_csr_attention_backward_workspace_bytes")
+        return int(out.value)
+
+    def csr_attention_backward(self, N, rowptr, colind, t_rowptr, t_colind, perm, Q, K, V, dO, dQ, dK, dV, H, d, scale,
+                               in_dt=BF16, hub_t=0, hub_chunk=0, workspace=None, stream=None, nnz=None):
+        nnz = int(colind.numel()) if nnz is None else nnz
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+        _check(_lib.autosage_csr_attention_backward(self._h, N, nnz, _ptr(rowptr), _ptr(colind), _ptr(t_rowptr), _ptr(t_colind),
+                                                    _ptr(perm), _ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(dQ), _ptr(dK),
+                                                    _ptr(dV), H, d, scale, in_dt, hub_t, hub_chunk, _ptr(workspace), ws_bytes,
+                                                    _stream(stream)), "autosage_csr_attention_backward")
+
     def hub_partition(self, n_rows, rowptr, hub_t, hub_chunk, hub_rows, chunk_ptr, light_rows, workspace, stream=None):
         """Fills the device tensors hub_rows / chunk_ptr / light_rows; returns (n_hub, n_light)."""
         nh, nl = ctypes.c_int32(), ctypes.c_int32()

@@ -795,6 +795,192 @@ extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autos
 }
 
 // ------------------------------------------------------------------------------------------
+// attention backward: the chain rule through the three stages, all heads at once
+// ------------------------------------------------------------------------------------------
+namespace autosage {
+
+// Workspace: P [nnz, H] | D [nnz, H] (dP, then dS) | T [nnz, H] (weights in the order of A^T) | hub partition
+// + partial buffer (partitioned for A first, for A^T afterwards).
+static size_t attention_bwd_hub_bytes(int64_t N, int64_t nnz, int32_t H, int32_t d, int hub_t, int chunk)
+{
+    return hub_workspace_bytes(N, nnz, hub_t, chunk, (int64_t)attention_part_floats(H, d));
+}
+
+static size_t attention_bwd_bytes(int64_t N, int64_t nnz, int32_t H, int32_t d, int hub_t, int chunk)
+{
+    const size_t cells = align_up(sizeof(float) * (size_t)(nnz > 0 ? nnz : 1) * H, 256);
+    return 3 * cells + attention_bwd_hub_bytes(N, nnz, H, d, hub_t, chunk);
+}
+
+struct AttnBwdCall {
+    int64_t N, nnz;
+    const int32_t *rowptr, *colind, *t_rowptr, *t_colind, *perm;
+    const void *Q, *K, *V;
+    const float* dO;
+    float *dQ, *dK, *dV;
+    int32_t H, d;
+    float scale;
+    int dt;
+};
+
+static autosage_status_t exec_attention_backward(autosage_ctx* h, const AttnBwdCall& c, int hub_t, int chunk, void* workspace,
+                                                 size_t workspace_bytes, hipStream_t st)
+{
+    const int32_t H = c.H, d = c.d;
+    const int64_t HD = (int64_t)H * d, N = c.N, nnz = c.nnz;
+    const RowMap rows{0, 1, (int32_t)N, 0};
+    autosage_schedule_t s{};
+    s.mapping = AUTOSAGE_MAP_WAVE_ROW;
+    s.vec_bytes = 16;
+    s.hub_t = hub_t;
+    s.hub_chunk = chunk;
+    Resolved rs, rp, rp32;
+    autosage_status_t rc = resolve_schedule(s, AUTOSAGE_OP_SDDMM, d, c.dt, H, 16, 16, &rs);
+    if (rc != AUTOSAGE_OK) return rc;
+    rc = resolve_schedule(s, AUTOSAGE_OP_SPMM, (int32_t)HD, c.dt, 1, 16, 16, &rp);
+    if (rc != AUTOSAGE_OK) return rc;
+    rc = resolve_schedule(s, AUTOSAGE_OP_SPMM, (int32_t)HD, DT_F32, 1, 16, 16, &rp32);
+    if (rc != AUTOSAGE_OK) return rc;
+
+    const size_t need = attention_bwd_bytes(N, nnz, H, d, rs.hub_t, rs.hub_chunk);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uint64_t>(workspace) & 255u) != 0)
+        return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+    const size_t cells = align_up(sizeof(float) * (size_t)(nnz > 0 ? nnz : 1) * H, 256);
+    char* base = static_cast<char*>(workspace);
+    float* P = reinterpret_cast<float*>(base);
+    float* D = reinterpret_cast<float*>(base + cells);
+    float* T = reinterpret_cast<float*>(base + 2 * cells);
+    void* hub_ws = base + 3 * cells;
+    const size_t hub_ws_bytes = workspace_bytes - 3 * cells;
+
+    HubMeta meta{};
+    float* part = nullptr;
+    auto partition = [&](const int32_t* rowptr) -> autosage_status_t {
+        if (rs.hub_t <= 0) return AUTOSAGE_OK;
+        if (!carve_hub(hub_ws, hub_ws_bytes, N, nnz, rs.hub_t, rs.hub_chunk, (int64_t)attention_part_floats(H, d), &meta, &part,
+                       nullptr))
+            return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
+        STAGE(h, "hub_partition", st, launch_hub_partition(rows, rowptr, rs.hub_t, rs.hub_chunk, meta, st));
+        return AUTOSAGE_OK;
+    };
+    auto sddmm = [&](const void* X, bool x_f32, const void* Y, float scale, float* out) -> autosage_status_t {
+        SddmmArgs a{};
+        a.rows = rows;
+        a.rowptr = c.rowptr;
+        a.colind = c.colind;
+        a.X = X;
+        a.ldx = HD;
+        a.Y = Y;
+        a.ldy = HD;
+        a.out = out;
+        a.F = d;
+        a.dt = c.dt;
+        a.heads = H;
+        a.scale = scale;
+        a.x_f32 = x_f32 ? 1 : 0;
+        STAGE(h, "attn_bwd_sddmm_rows", st, launch_sddmm_rows(a, rs, st));
+        if (rs.hub_t > 0) STAGE(h, "attn_bwd_sddmm_hub", st, launch_sddmm_hub(a, rs, meta, st));
+        return AUTOSAGE_OK;
+    };
+    auto spmm = [&](const int32_t* rowptr, const int32_t* colind, const float* w, const void* B, int dt, const Resolved& r,
+                    float* out) -> autosage_status_t {
+        SpmmArgs a{};
+        a.rows = rows;
+        a.rowptr = rowptr;
+        a.colind = colind;
+        a.val = w;
+        a.B = B;
+        a.ldb = HD;
+        a.C = out;
+        a.ldc = HD;
+        a.F = (int32_t)HD;
+        a.dt = dt;
+        a.heads = H > 1 ? H : 1;
+        a.head_dim = d;
+        STAGE(h, "attn_bwd_spmm_rows", st, launch_spmm_rows(a, r, st));
+        if (r.hub_t > 0) STAGE(h, "attn_bwd_spmm_hub", st, launch_spmm_hub(a, r, meta, part, st));
+        return AUTOSAGE_OK;
+    };
+
+    // forward pattern: P = softmax(scale * Q K^T), dP = <dO, V>, dS = scale * softmax'(P, dP), dQ = dS K
+    rc = partition(c.rowptr);
+    if (rc != AUTOSAGE_OK) return rc;
+    if (nnz > 0) {
+        rc = sddmm(c.Q, false, c.K, c.scale, P);
+        if (rc != AUTOSAGE_OK) return rc;
+        SoftmaxArgs ma{};
+        ma.rows = rows;
+        ma.rowptr = c.rowptr;
+        ma.in = P;
+        ma.out = P;
+        ma.H = H;
+        rc = exec_softmax(h, ma, nnz, rs.hub_t, rs.hub_chunk, rs.wpg, rs.hub_t > 0 ? &meta : nullptr, part, nullptr, 0, st);
+        if (rc != AUTOSAGE_OK) return rc;
+        rc = sddmm(c.dO, true, c.V, 1.0f, D);
+        if (rc != AUTOSAGE_OK) return rc;
+        SoftmaxBwdArgs ba{};
+        ba.rows = rows;
+        ba.rowptr = c.rowptr;
+        ba.P = P;
+        ba.dP = D;
+        ba.dS = D;
+        ba.H = H;
+        ba.scale = c.scale;
+        STAGE(h, "attn_bwd_softmax", st, launch_softmax_bwd(ba, rs.hub_t, rs.hub_chunk, rs.hub_t > 0 ? &meta : nullptr, part, st));
+    }
+    rc = spmm(c.rowptr, c.colind, D, c.K, c.dt, rp, c.dQ);
+    if (rc != AUTOSAGE_OK) return rc;
+
+    // transposed pattern: dV = P^T dO, dK = dS^T Q
+    rc = partition(c.t_rowptr);
+    if (rc != AUTOSAGE_OK) return rc;
+    if (nnz > 0) STAGE(h, "gather_values", st, launch_gather_rows(c.perm, nnz, H, P, T, st));
+    rc = spmm(c.t_rowptr, c.t_colind, T, c.dO, DT_F32, rp32, c.dV);
+    if (rc != AUTOSAGE_OK) return rc;
+    if (nnz > 0) STAGE(h, "gather_values", st, launch_gather_rows(c.perm, nnz, H, D, T, st));
+    return spmm(c.t_rowptr, c.t_colind, T, c.Q, c.dt, rp, c.dK);
+}
+
+}  // namespace autosage
+
+extern "C" autosage_status_t autosage_csr_attention_backward_workspace_bytes(autosage_handle_t h, int64_t N, int64_t nnz,
+                                                                             int32_t H, int32_t d, int32_t hub_t,
+                                                                             int32_t hub_chunk, size_t* bytes)
+{
+    if (!h || !bytes || !sizes_ok(N, N, nnz) || H <= 0 || d <= 0 || hub_t < 0 || hub_chunk < 0) return AUTOSAGE_ERR_INVALID_ARG;
+    const int chunk = effective_hub_chunk(hub_t, hub_chunk);
+    if (hub_t > 0 && (hub_t < kMinHubT || chunk < kMinHubT || chunk > kMaxHubChunk)) return AUTOSAGE_ERR_INVALID_ARG;
+    *bytes = attention_bwd_bytes(N, nnz, H, d, hub_t, chunk);
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_csr_attention_backward(
+    autosage_handle_t h, int64_t N, int64_t nnz, const int32_t* rowptr, const int32_t* colind, const int32_t* t_rowptr,
+    const int32_t* t_colind, const int32_t* perm, const void* Q, const void* K, const void* V, const float* dO, float* dQ,
+    float* dK, float* dV, int32_t H, int32_t d, float scale, autosage_dtype_t in_dt, int32_t hub_t, int32_t hub_chunk,
+    void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!h || !sizes_ok(N, N, nnz) || H <= 0 || d <= 0 || (int64_t)H * d >= (1 << 24) || hub_t < 0 || hub_chunk < 0)
+        return AUTOSAGE_ERR_INVALID_ARG;
+    if (!dtype_known(in_dt)) return AUTOSAGE_ERR_INVALID_ARG;
+    const int chunk = effective_hub_chunk(hub_t, hub_chunk);
+    if (hub_t > 0 && (hub_t < kMinHubT || chunk < kMinHubT || chunk > kMaxHubChunk)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (N == 0) return AUTOSAGE_OK;
+    if (!rowptr || !t_rowptr || !dQ || !dK || !dV) return AUTOSAGE_ERR_INVALID_ARG;
+    if (nnz > 0 && (!colind || !t_colind || !perm || !Q || !K || !V || !dO)) return AUTOSAGE_ERR_INVALID_ARG;
+    // the forward's alignment rule for Q, K, V; the fp32 tensors are read and written in 16-byte pieces
+    AttnCall fc{N, nnz, rowptr, colind, Q, K, V, dQ, H, d, scale, (int)in_dt};
+    autosage_status_t rc = attention_alignment(fc);
+    if (rc != AUTOSAGE_OK) return rc;
+    const int64_t HD = (int64_t)H * d;
+    if (d % 4 != 0 || common_alignment(dO, HD, 4) < 16 || common_alignment(dK, HD, 4) < 16 || common_alignment(dV, HD, 4) < 16)
+        return AUTOSAGE_ERR_UNSUPPORTED;
+    AttnBwdCall c{N, nnz, rowptr, colind, t_rowptr, t_colind, perm, Q, K, V, dO, dQ, dK, dV, H, d, scale, (int)in_dt};
+    return exec_attention_backward(h, c, hub_t, chunk, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+// ------------------------------------------------------------------------------------------
 // plan / metadata
 // ------------------------------------------------------------------------------------------
 extern "C" autosage_status_t autosage_hub_partition(autosage_handle_t h, int64_t n_rows, const int32_t* rowptr,

@@ -34,6 +34,12 @@ template <> struct VecIO<float, 4> {
         float4 t = *reinterpret_cast<const float4*>(p); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     }
 };
+template <> struct VecIO<float, 8> {
+    static __device__ __forceinline__ void load(const float* p, float* v) {
+        float4 t = *reinterpret_cast<const float4*>(p), u = *reinterpret_cast<const float4*>(p + 4);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; v[4] = u.x; v[5] = u.y; v[6] = u.z; v[7] = u.w;
+    }
+};
 template <> struct VecIO<bf16_t, 1> {
     static __device__ __forceinline__ void load(const bf16_t* p, float* v) { v[0] = bf16_bits_to_f32(p->bits); }
 };

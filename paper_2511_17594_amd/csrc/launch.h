@@ -89,6 +89,7 @@ struct SddmmArgs {
     int32_t dt;
     int32_t heads;
     float scale;           // out = scale * dot
+    int32_t x_f32;         // 1: X holds fp32 whatever dt says (Y keeps dt): the upstream gradient against 16-bit V
 };
 
 struct SoftmaxArgs {
@@ -139,6 +140,7 @@ struct SoftmaxBwdArgs {
     const float* dP;       // [nnz, H] gradient with respect to P (may alias dS)
     float* dS;             // [nnz, H] gradient with respect to the scores
     int32_t H;
+    float scale;           // dS is multiplied by it (the chain rule through scaled scores); 0 means 1
 };
 
 // dS = P * (dP - rowsum(P * dP)); hub rows (degree >= hub_t) through per-chunk partial dots in `part` ([cap_chunks, H]).

@@ -235,6 +235,7 @@ struct SoftmaxBwdDev {
     const float* P;
     const float* dP;        // may alias dS
     float* dS;
+    float scale;
     int32_t H;
     int32_t hp_shift;
     int32_t hub_t;
@@ -274,7 +275,7 @@ __global__ void __launch_bounds__(1024) softmax_bwd_rows_kernel(SoftmaxBwdDev a)
         if (hv) {
             for (int p = p0 + pl; p < p1; p += PL) {
                 const int64_t e = (int64_t)p * a.H + h;
-                a.dS[e] = a.P[e] * (a.dP[e] - dot);
+                a.dS[e] = a.scale * (a.P[e] * (a.dP[e] - dot));
             }
         }
     }
@@ -344,7 +345,7 @@ __global__ void __launch_bounds__(1024) softmax_bwd_hub_apply_kernel(SoftmaxBwdD
         for (int c = c0; c < c1; ++c) dot += a.part[(int64_t)c * a.H + h];   // ascending chunk order
         for (int p = q0 + wave * PL + pl; p < q1; p += wpg * PL) {
             const int64_t e = (int64_t)p * a.H + h;
-            a.dS[e] = a.P[e] * (a.dP[e] - dot);
+            a.dS[e] = a.scale * (a.P[e] * (a.dP[e] - dot));
         }
     }
 }
@@ -405,6 +406,7 @@ hipError_t launch_softmax_bwd(const SoftmaxBwdArgs& a, int32_t hub_t, int32_t hu
     d.P = a.P;
     d.dP = a.dP;
     d.dS = a.dS;
+    d.scale = a.scale == 0.f ? 1.f : a.scale;
     d.H = a.H;
     d.hp_shift = log2_ceil_pow2(a.H < kWave ? a.H : kWave);
     d.hub_t = hub_t;

@@ -262,28 +262,20 @@ def _attention_setup(ctx, inputs, output):
 
 
 def _attention_backward(ctx, dO):
-    """Head by head, with the library's operators on strided views of the [N, H, d] tensors:
-    S = scale * SDDMM(Q, K), P = softmax(S), dV = P^T dO, dP = SDDMM(dO, V), dS = softmax'(P, dP),
-    dQ = scale * dS K, dK = scale * dS^T Q.  (The probabilities are recomputed, not stored.)"""
+    """One library call (autosage_csr_attention_backward): probabilities recomputed from Q and K, then
+    dV = P^T dO, dP = <dO, V>, dS = scale * softmax'(P, dP), dQ = dS K, dK = dS^T Q, all heads at once."""
     rowptr, colind, Q, K, V = ctx.saved_tensors
-    scale = ctx.scale
+    h = handle(Q.device)
     N, H, d = Q.shape
-    Qf, Kf, Vf = (t.float().contiguous() for t in (Q, K, V))
+    nnz = colind.numel()
+    Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
     dO = dO.float().contiguous()
     t_rowptr, t_colind, perm = transpose(rowptr, colind, N)
     dQ, dK, dV = (torch.empty((N, H, d), dtype=torch.float32, device=Q.device) for _ in range(3))
-    HD = H * d
-    for hd in range(H):
-        q, k, v, g = (t[:, hd, :] for t in (Qf, Kf, Vf, dO))           # views with leading dimension H*d
-        S = _sddmm(rowptr, colind, q, k, ldx=HD, ldy=HD, F=d)
-        S.mul_(scale)
-        P = csr_row_softmax(rowptr, S)
-        _spmm(t_rowptr, t_colind, _gather(perm, P), g, None, n_rows=N, ldb=HD, out=dV[:, hd, :], ldc=HD, F=d)
-        dP = _sddmm(rowptr, colind, g, v, ldx=HD, ldy=HD, F=d)
-        dS = _softmax_backward_raw(rowptr, P, dP)
-        dS.mul_(scale)
-        _spmm(rowptr, colind, dS, k, None, ldb=HD, out=dQ[:, hd, :], ldc=HD, F=d)
-        _spmm(t_rowptr, t_colind, _gather(perm, dS), q, None, n_rows=N, ldb=HD, out=dK[:, hd, :], ldc=HD, F=d)
+    hub = 512            # rows of the pattern, and of its transpose, this long are split over workgroups
+    ws = _ws(h.csr_attention_backward_workspace_bytes(N, nnz, H, d, hub), Q.device)
+    h.csr_attention_backward(N, rowptr, colind, t_rowptr, t_colind, perm, Q, K, V, dO, dQ, dK, dV, H, d, ctx.scale,
+                             in_dt=_dt(Q), hub_t=hub, workspace=ws, nnz=nnz)
     return None, None, dQ.to(Q.dtype), dK.to(K.dtype), dV.to(V.dtype), None
 
 

@@ -123,3 +123,78 @@ def test_softmax_backward(torch, handle, ab, H, hub_t):
     handle.csr_row_softmax_backward(A.n_rows, A.nnz, d_rp, d_P, d_dP, d_dP, H=H, hub_t=hub_t, workspace=ws)
     torch.cuda.synchronize()
     assert np.array_equal(d_dP.cpu().numpy(), got)
+
+
+def as_f64(t, shape):
+    if t.dtype == np.uint16:
+        return W.bf16_bits_to_float(t).reshape(shape).astype(np.float64)
+    return np.asarray(t, dtype=np.float64).reshape(shape)
+
+
+def gradient_term_magnitudes(A, Q, K, V, dO, scale):
+    """The sums of the magnitudes of the terms of dQ, dK, dV (the same chain rule on absolute values, with the
+    oracle's probabilities): the scale of the rounding error of a gradient that cancels, e.g. under a
+    saturated softmax where dS = P (dP - sum P dP) is a difference of nearly equal numbers."""
+    n, H, d = dO.shape
+    _, _, P = oracle.csr_attention(A.rowptr, A.colind, Q, K, V, scale, return_scores=True)
+    rows = np.repeat(np.arange(n), A.degrees)
+    cols = A.colind.astype(np.int64)
+    q, k, v, g = (np.abs(as_f64(t, (n, H, d))) for t in (Q, K, V, dO))
+    adP = np.einsum("phk,phk->ph", g[rows], v[cols])
+    rowdot = np.zeros((n, H))
+    np.add.at(rowdot, rows, P * adP)
+    adS = scale * P * (adP + rowdot[rows])
+    mQ, mK, mV = (np.zeros((n, H, d)) for _ in range(3))
+    np.add.at(mQ, rows, adS[:, :, None] * k[cols])
+    np.add.at(mK, cols, adS[:, :, None] * q[rows])
+    np.add.at(mV, cols, P[:, :, None] * g[rows])
+    return mQ, mK, mV
+
+
+@pytest.mark.parametrize("H,d,dtype,hub_t,qk_std", [
+    (8, 64, "bf16", 256, 1.0), (8, 64, "bf16", 0, None), (2, 32, "f16", 128, 2.0), (1, 128, "bf16", 64, 1.0),
+    (4, 16, "f32", 256, 1.0), (3, 16, "bf16", 512, 1.0), (8, 64, "f32", 0, 1.0),
+])
+def test_attention_backward(torch, handle, ab, H, d, dtype, hub_t, qk_std):
+    """dQ, dK, dV of the library against the oracle's chain rule, on a skewed square pattern with hub rows in
+    the pattern and in its transpose, empty rows, and columns nobody attends to."""
+    from util import dtype_code
+    n = 3001
+    A = skew(n, n - 40, seed=900 + H + d)
+    A = W.CSR(n, n, A.rowptr, A.colind, A.val)          # square, the last 40 columns never attended to
+    Qb, Kb, Vb = W.config5_attention(n, H, d, seed=H * 10 + d, qk_std=qk_std)
+    if dtype == "bf16":
+        Q, K, V, tol = Qb, Kb, Vb, 2e-2
+    elif dtype == "f16":
+        Q, K, V = (W.bf16_bits_to_float(t).reshape(n, H, d).astype(np.float16) for t in (Qb, Kb, Vb))
+        tol = 2e-2
+    else:
+        Q, K, V = (np.ascontiguousarray(W.bf16_bits_to_float(t).reshape(n, H, d) * np.float32(1.001), dtype=np.float32)
+                   for t in (Qb, Kb, Vb))
+        tol = 1e-4                                     # six fp32 stages stacked on each other
+    scale = float(d) ** -0.5
+    dO = np.random.default_rng(5).standard_normal((n, H, d)).astype(np.float32)
+    ref = oracle.csr_attention_backward(A.rowptr, A.colind, Q, K, V, dO, scale)
+    ref_abs = gradient_term_magnitudes(A, Q, K, V, dO, scale)
+    t_rowptr, t_colind, _, perm = gpu_transpose(torch, handle, A, with_val=False)
+    outs = [torch.full((n, H, d), float("nan"), dtype=torch.float32, device="cuda") for _ in range(3)]
+    ws = torch.empty(handle.csr_attention_backward_workspace_bytes(n, A.nnz, H, d, hub_t), dtype=torch.uint8, device="cuda")
+    print("attention backward H %d d %d %s hub %d" % (H, d, dtype, hub_t), flush=True)
+    handle.csr_attention_backward(n, dev(A.rowptr, torch), dev(A.colind, torch), t_rowptr, t_colind, perm,
+                                  dev(Q, torch), dev(K, torch), dev(V, torch), dev(dO, torch), *outs, H, d, scale,
+                                  in_dt=dtype_code(ab, Q), hub_t=hub_t, workspace=ws, nnz=A.nnz)
+    torch.cuda.synchronize()
+    unused = np.setdiff1d(np.arange(n), A.colind)
+    assert unused.size > 0
+    for name, got_t, want, mag in zip(("dQ", "dK", "dV"), outs, ref, ref_abs):
+        got = got_t.cpu().numpy()
+        assert np.isfinite(got).all(), name
+        err = rel_l1_rows(got.reshape(n * H, d), want.reshape(n * H, d), mag.reshape(n * H, d))
+        # rows whose gradient vanishes (empty rows, unused columns) must be exactly zero; the rest within tolerance
+        zero = np.abs(want.reshape(n * H, d)).sum(axis=1) == 0
+        assert np.all(got.reshape(n * H, d)[zero] == 0.0), name
+        assert err[~zero].max() <= tol, (name, float(err[~zero].max()), int(np.argmax(err * ~zero)))
+        if dtype != "f32":
+            assert err[~zero].max() <= 5e-4, (name, float(err[~zero].max()))     # exact inputs, fp32 arithmetic only
+    assert np.all(outs[1].cpu().numpy()[unused] == 0.0) and np.all(outs[2].cpu().numpy()[unused] == 0.0)
+    assert np.all(outs[0].cpu().numpy()[A.degrees == 0] == 0.0)
