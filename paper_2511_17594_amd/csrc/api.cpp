@@ -157,8 +157,9 @@ autosage_status_t resolve_schedule(const autosage_schedule_t& s, int op, int32_t
     r.tiles = (F + r.f_tile - 1) / r.f_tile;
 
     if (op == AUTOSAGE_OP_SDDMM) {
-        // the dot product of one head must sit in one pass of one group
-        if (r.tiles != 1) {
+        // A dot product sits in one pass of one group, except for an explicit narrower tile with one head:
+        // then the tiles run as consecutive launches that add their partial dots into the output.
+        if (r.tiles != 1 && !(s.f_tile > 0 && heads == 1)) {
             r.G = 64;
             r.K = round_chunks((lanes_needed + 63) / 64);
             if ((lanes_needed + 63) / 64 > 8) return AUTOSAGE_ERR_UNSUPPORTED;
@@ -283,6 +284,24 @@ autosage_status_t exec_sddmm(autosage_ctx* h, const SddmmArgs& a, const Resolved
         if (!carve_hub(ws, ws_bytes, a.rows.count, nnz, r.hub_t, r.hub_chunk, 0, &meta, nullptr, nullptr))
             return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
         STAGE(h, "hub_partition", st, launch_hub_partition(a.rows, a.rowptr, r.hub_t, r.hub_chunk, meta, st));
+    }
+    if (r.tiles > 1 && r.mapping != MAP_PLAIN) {
+        // feature tiles one after the other (stream order makes the read-modify-write of `out` safe): the slice
+        // of Y that a tile gathers from is n_cols * f_tile elements, small enough to stay in the caches
+        const int ex = a.x_f32 ? 4 : dtype_bytes(a.dt), ey = dtype_bytes(a.dt);
+        Resolved rt = r;
+        rt.tiles = 1;
+        for (int t = 0; t < r.tiles; ++t) {
+            SddmmArgs at = a;
+            const int f0 = t * r.f_tile;
+            at.X = static_cast<const char*>(a.X) + (size_t)f0 * ex;
+            at.Y = static_cast<const char*>(a.Y) + (size_t)f0 * ey;
+            at.F = std::min(r.f_tile, a.F - f0);
+            at.accumulate = t > 0 ? 1 : 0;
+            STAGE(h, "sddmm_rows", st, launch_sddmm_rows(at, rt, st));
+            if (r.hub_t > 0) STAGE(h, "sddmm_hub", st, launch_sddmm_hub(at, rt, meta, st));
+        }
+        return AUTOSAGE_OK;
     }
     STAGE(h, "sddmm_rows", st, launch_sddmm_rows(a, r, st));
     if (r.hub_t > 0) STAGE(h, "sddmm_hub", st, launch_sddmm_hub(a, r, meta, st));

@@ -105,6 +105,7 @@ constexpr int kMaxHubChunk = 1 << 20;                                  // longes
 constexpr int64_t kMaxNnz = (int64_t(1) << 31) - (int64_t(1) << 20);   // most nonzeros, and most rows, of a call
 constexpr int kSelectorMinHubT = 512;      // smallest threshold the selector proposes for SpMM / SDDMM
 constexpr int kSelectorMinChunk = 256;     // shortest hub chunk the selector proposes
+constexpr double kTileOperandBytes = 96.0 * 1024 * 1024;   // dense operands above this get narrow-tile candidates
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

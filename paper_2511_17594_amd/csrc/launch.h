@@ -90,6 +90,7 @@ struct SddmmArgs {
     int32_t heads;
     float scale;           // out = scale * dot
     int32_t x_f32;         // 1: X holds fp32 whatever dt says (Y keeps dt): the upstream gradient against 16-bit V
+    int32_t accumulate;    // 1: out += scale * dot (feature tiles after the first)
 };
 
 struct SoftmaxArgs {

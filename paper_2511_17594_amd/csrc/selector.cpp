@@ -156,7 +156,6 @@ void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, in
                int64_t max_deg, int32_t F, int dt, int align_bytes, std::vector<autosage_schedule_t>* out,
                std::vector<double>* est)
 {
-    (void)n_cols;
     Model m;
     if (h && h->cu_count > 0) m.waves = h->cu_count * 32;
     const int esize = dtype_bytes(dt);
@@ -165,8 +164,21 @@ void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, in
     std::vector<std::pair<double, autosage_schedule_t>> all;
     const int hubs[] = {0, 512, 1024, 2048, 4096};
     const int unrolls[] = {4, 8, 2};
+    // Narrow feature tiles (SpMM, one wavefront per row): the launch walks the tiles one after the other, so a
+    // dense operand too large for the caches is worked through in slices of n_cols * tile bytes that fit them,
+    // at the price of reading the indices once per tile.  The histogram knows nothing of locality, so these
+    // are ranked by the same estimate and the caller probes the best of each tile width.  (SDDMM accepts an
+    // explicit narrow tile too, one launch per tile, but measured no gain from it, so none is proposed.)
+    std::vector<int> ftiles{0};
+    if (op == AUTOSAGE_OP_SPMM && p.force_ftile <= 0 && (int64_t)F * esize >= 512 &&
+        (double)n_cols * F * esize >= kTileOperandBytes) {
+        ftiles.push_back(256 / esize);
+        ftiles.push_back(512 / esize);
+    }
     for (int mapping = AUTOSAGE_MAP_WAVE_ROW; mapping <= AUTOSAGE_MAP_MULTI_ROW; ++mapping) {
         for (int vb = 16; vb >= esize; vb >>= 1) {
+          for (int ft : ftiles) {
+            if (ft > 0 && (mapping != AUTOSAGE_MAP_WAVE_ROW || ft >= F || vb < 8)) continue;
             for (int u : unrolls) {
                 for (int hub : hubs) {
                     if (hub > 0 && max_deg < hub) continue;
@@ -174,7 +186,7 @@ void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, in
                     for (int xcd = 0; xcd <= 1; ++xcd) {
                         autosage_schedule_t s{};
                         s.mapping = mapping;
-                        s.f_tile = p.force_ftile > 0 ? p.force_ftile : 0;
+                        s.f_tile = p.force_ftile > 0 ? p.force_ftile : ft;
                         s.waves_per_wg = p.force_wpb > 0 ? p.force_wpb : 4;
                         s.vec_bytes = vb;
                         s.unroll = u;
@@ -195,6 +207,7 @@ void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, in
                     }
                 }
             }
+          }
         }
     }
     std::stable_sort(all.begin(), all.end(), [](const auto& a, const auto& b) { return a.first < b.first; });
@@ -579,6 +592,7 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
         if (op == AUTOSAGE_OP_ATTENTION) shortlist_attention(h, nnz, hist, max_deg, in.H, F, dt, &all, &all_est);
         else shortlist(h, op, n_rows, n_cols, nnz, hist, max_deg, F, dt, al, &all, &all_est);
         for (size_t i = 0; i < all.size() && (int)cands.size() < h->params.probe_topk; ++i) {
+            if (all[i].f_tile != 0 && h->params.force_ftile <= 0) continue;      // narrow tiles: below
             bool fresh = true;
             for (const autosage_schedule_t& c : cands)
                 if (c.mapping == all[i].mapping && c.hub_t == all[i].hub_t && c.xcd_remap == all[i].xcd_remap &&
@@ -587,6 +601,20 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
             if (fresh) {
                 cands.push_back(all[i]);
                 est.push_back(all_est[i]);
+            }
+        }
+        // the best-ranked candidate of every narrow tile width, with and without the XCD-aware launch, is
+        // probed on top of the k above (their gain is a cache effect that the estimate cannot see)
+        if (h->params.force_ftile <= 0) {
+            for (size_t i = 0; i < all.size(); ++i) {
+                if (all[i].f_tile == 0) continue;
+                bool fresh = true;
+                for (const autosage_schedule_t& c : cands)
+                    if (c.f_tile == all[i].f_tile && c.xcd_remap == all[i].xcd_remap) fresh = false;
+                if (fresh) {
+                    cands.push_back(all[i]);
+                    est.push_back(all_est[i]);
+                }
             }
         }
     }

@@ -88,7 +88,8 @@ def main(argv=None):
 
     def short(c):
         m = {0: "plain", 1: "wave-row", 2: "multi-row"}[c["mapping"]]
-        return "%s v%d u%d hub %d%s" % (m, c["vec_bytes"], c["unroll"], c["hub_t"], " xcd" if c["xcd_remap"] else "")
+        return "%s v%d u%d hub %d%s%s" % (m, c["vec_bytes"], c["unroll"], c["hub_t"],
+                                          " tile %d" % c["f_tile"] if c["f_tile"] else "", " xcd" if c["xcd_remap"] else "")
 
     print("| op | F | ms | GFLOP/s | GB/s | of 8 TB/s | fallback ms | speed-up | cold call ms | selector's choice |")
     print("|---|---|---|---|---|---|---|---|---|---|")

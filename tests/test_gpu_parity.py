@@ -91,6 +91,8 @@ SCHEDULES = [
     dict(mapping=1, hub_t=512, waves_per_wg=8),
     dict(mapping=2),                                              # several rows per wavefront
     dict(mapping=2, hub_t=1024, unroll=2, xcd_remap=1, waves_per_wg=2),
+    dict(mapping=1, f_tile=64, hub_t=256, xcd_remap=1),           # narrow feature tiles (SDDMM: one launch per tile)
+    dict(mapping=1, f_tile=32, vec_bytes=4),
 ]
 
 
