@@ -4,12 +4,13 @@
 
 For every width: the selector's choice (cold call, then steady state from its cache), time (median of
 `--iters` HIP-event timings), GFLOP/s = 2*nnz*F/t, algorithmic GB/s (every gathered dense row counted
-once per nonzero; `--dtype bf16` / `f16` halve the bytes of a gathered row) and its fraction of the 8 TB/s HBM peak, and the guardrail's fallback kernel on the
-same input.  `--vendor` adds the vendor SpMM reached through torch.sparse.mm.  Workloads: config1..4
-(the benchmark configurations), er (Erdos-Renyi N = 200000, p = 2e-5, the shape of the paper's
-extreme-sparsity stressor) and hubsplit_5k / hubsplit_12k (N = 20000, a few rows of degree 5000 /
-12000, the rest 64 / 32: the shape of the paper's split-versus-baseline table; the number of hub rows
-is not given there, 32 is used).
+once per nonzero; `--dtype bf16` / `f16` halve the bytes of a gathered row) and its fraction of the
+8 TB/s HBM peak, the rate in compulsory bytes (every array touched exactly once), and the guardrail's
+fallback kernel on the same input.  `--vendor` adds the vendor SpMM reached through torch.sparse.mm.
+Workloads: config1..4 (the benchmark configurations), er (Erdos-Renyi N = 200000, p = 2e-5, the shape of
+the paper's extreme-sparsity stressor) and hubsplit_5k / hubsplit_12k (N = 20000, a few rows of degree
+5000 / 12000, the rest 64 / 32: the shape of the paper's split-versus-baseline table; the number of hub
+rows is not given there, 32 is used).
 """
 from __future__ import annotations
 
@@ -91,8 +92,8 @@ def main(argv=None):
         return "%s v%d u%d hub %d%s%s" % (m, c["vec_bytes"], c["unroll"], c["hub_t"],
                                           " tile %d" % c["f_tile"] if c["f_tile"] else "", " xcd" if c["xcd_remap"] else "")
 
-    print("| op | F | ms | GFLOP/s | GB/s | of 8 TB/s | fallback ms | speed-up | cold call ms | selector's choice |")
-    print("|---|---|---|---|---|---|---|---|---|---|")
+    print("| op | F | ms | GFLOP/s | GB/s | of 8 TB/s | compulsory GB/s | fallback ms | speed-up | cold call ms | selector's choice |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
     for F in widths:
         g = torch.Generator(device="cuda").manual_seed(F)
         B = torch.randn((M, F), device="cuda", generator=g)
@@ -106,6 +107,9 @@ def main(argv=None):
         esz = 4 if args.dtype == "f32" else 2
         dt = {"f32": ab.F32, "bf16": ab.BF16, "f16": ab.F16}[args.dtype]
         bg = 4 * (N + 1) + 8 * nnz + nnz * F * esz + N * F * 4
+        # compulsory bytes (every array touched once): SpMM reads B and writes C, SDDMM reads X and Y and writes out
+        bmin = {"SpMM": 4 * (N + 1) + 8 * nnz + M * F * esz + N * F * 4,
+                "SDDMM": 4 * (N + 1) + 4 * nnz + (N + M) * F * esz + 4 * nnz}
         ops = [("SpMM", lambda s: h.spmm(N, M, rp, ci, va, B, C, F, dt=dt, sched=s, workspace=ws, stream=stream))]
         if not args.no_sddmm:
             ops.append(("SDDMM", lambda s: h.sddmm(N, M, rp, ci, X, B, out, F, dt=dt, sched=s, workspace=ws, stream=stream,
@@ -119,15 +123,16 @@ def main(argv=None):
             choice = h.last_decision().get("choice")
             t = timed(lambda: fn(None), args.iters)
             tb = timed(lambda: fn(base), 3)
-            print("| %s | %d | %.3f | %.0f | %.0f | %.0f %% | %.3f | %.2fx | %.1f | %s |"
-                  % (name, F, t, 2.0 * nnz * F / t / 1e6, bg / t / 1e6, 100 * bg / t / 1e6 / HBM_PEAK_GBS, tb, tb / t, cold,
-                     short(choice)), flush=True)
+            print("| %s | %d | %.3f | %.0f | %.0f | %.0f %% | %.0f | %.3f | %.2fx | %.1f | %s |"
+                  % (name, F, t, 2.0 * nnz * F / t / 1e6, bg / t / 1e6, 100 * bg / t / 1e6 / HBM_PEAK_GBS, bmin[name] / t / 1e6,
+                     tb, tb / t, cold, short(choice)), flush=True)
         if args.vendor and args.dtype == "f32":
             try:
                 Asp = torch.sparse_csr_tensor(rp.to(torch.int64), ci.to(torch.int64), va, size=(N, M))
                 tv = timed(lambda: torch.sparse.mm(Asp, B), 3)
-                print("| vendor SpMM (torch.sparse.mm) | %d | %.3f | %.0f | %.0f | %.0f %% | | | | |"
-                      % (F, tv, 2.0 * nnz * F / tv / 1e6, bg / tv / 1e6, 100 * bg / tv / 1e6 / HBM_PEAK_GBS), flush=True)
+                print("| vendor SpMM (torch.sparse.mm) | %d | %.3f | %.0f | %.0f | %.0f %% | %.0f | | | | |"
+                      % (F, tv, 2.0 * nnz * F / tv / 1e6, bg / tv / 1e6, 100 * bg / tv / 1e6 / HBM_PEAK_GBS,
+                         bmin["SpMM"] / tv / 1e6), flush=True)
                 del Asp
             except Exception as e:                      # pragma: no cover
                 print("vendor SpMM unavailable: %r" % (e,), file=sys.stderr)
