@@ -239,7 +239,7 @@ extern "C" autosage_status_t autosage_shortlist(autosage_handle_t h, autosage_op
 {
     if (!h || !hist33 || !n_out || max_out < 0 || (max_out > 0 && !out) || F <= 0 || n_rows < 0 || nnz < 0)
         return AUTOSAGE_ERR_INVALID_ARG;
-    if (op != AUTOSAGE_OP_SPMM && op != AUTOSAGE_OP_SDDMM) return AUTOSAGE_ERR_INVALID_ARG;
+    if ((op != AUTOSAGE_OP_SPMM && op != AUTOSAGE_OP_SDDMM) || !dtype_known(dt)) return AUTOSAGE_ERR_INVALID_ARG;
     if (align_bytes < 1 || (align_bytes & (align_bytes - 1)) != 0) return AUTOSAGE_ERR_INVALID_ARG;
     std::vector<autosage_schedule_t> c;
     std::vector<double> e;
