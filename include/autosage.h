@@ -103,8 +103,11 @@ autosage_status_t autosage_create(autosage_handle_t* out, int device_id);
 autosage_status_t autosage_destroy(autosage_handle_t h);
 const char* autosage_status_string(autosage_status_t s);
 
-/* Sets a selector parameter by name: "alpha", "probe_frac", "probe_iters", "probe_cap_ms",
+/* Sets a parameter by name.  Selector: "alpha", "probe_frac", "probe_iters", "probe_cap_ms",
  * "probe_topk", "probe_min_rows", "replay_only", "confirm_full", "memoize_signature".
+ * Row-softmax (forward and backward): "softmax_group" = lanes that share one light row (rounded up to
+ * a power of two <= 64, at least the lanes one entry of H heads takes); 0 (default) derives it from
+ * the mean row length, a negative value keeps one wavefront per row.
  * Unknown name -> AUTOSAGE_ERR_INVALID_ARG. */
 autosage_status_t autosage_set_param(autosage_handle_t h, const char* name, double value);
 autosage_status_t autosage_get_param(autosage_handle_t h, const char* name, double* value);
@@ -134,7 +137,10 @@ autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows, int64_t n_
 /* Row-softmax (Kernel templates: numerically stable CSR row-softmax).  in/out are [nnz, H] fp32
  * dev arrays (head index minor); for each row and head: m = max, e = exp(s - m), out = e / sum e.
  * Rows without nonzeros write nothing.  out may equal in.  hub_t > 0 splits rows of degree
- * >= hub_t into chunks of hub_chunk (0 = hub_t) entries with a two-pass combine (needs workspace). */
+ * >= hub_t into chunks of hub_chunk (0 = hub_t) entries: per-chunk (max, sum), one merge per row in a
+ * fixed order, then a normalising pass (needs workspace).  A power-of-two H <= 256 with in and out
+ * aligned to min(H, 4) floats takes vector loads with several short rows per wavefront; any other H
+ * or alignment runs one wavefront per row with scalar loads (same result within rounding). */
 autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64_t n_rows, int64_t nnz,
                                            const int32_t* rowptr, const float* in, float* out,
                                            int32_t H, int32_t hub_t, int32_t hub_chunk,

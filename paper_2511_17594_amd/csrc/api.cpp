@@ -436,6 +436,7 @@ static bool param_access(Params& p, const char* name, double* value, bool set)
     P_INT("force_ftile", force_ftile)
     P_INT("force_wpb", force_wpb)
     P_INT("force_hub_t", force_hub_t)
+    P_INT("softmax_group", softmax_group)
 #undef P_DOUBLE
 #undef P_INT
     return false;
@@ -563,6 +564,19 @@ extern "C" autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows,
     return exec_sddmm(h, a, r, nnz, workspace, workspace_bytes, st);
 }
 
+// Lanes per light row of the row-softmax kernels: the smallest power of two whose registers hold a row of
+// the mean length (16 floats per lane with vector loads, 8 with scalar loads); longer rows of the launch
+// are taken by whole wavefronts.
+static int softmax_group(const autosage_ctx* h, int64_t count, int64_t nnz, int H)
+{
+    if (h->params.softmax_group != 0) return h->params.softmax_group;
+    const int lane_floats = H >= 2 ? 16 : 8;
+    const double want = (double)nnz / (double)(count > 0 ? count : 1) * H;
+    int g = 1;
+    while (g < 64 && g * lane_floats < want) g <<= 1;
+    return g;
+}
+
 static autosage_status_t exec_softmax(autosage_ctx* h, const SoftmaxArgs& a, int64_t nnz, int hub_t, int hub_chunk, int wpg,
                                       const HubMeta* shared_meta, float* shared_part, void* ws, size_t ws_bytes,
                                       hipStream_t st)
@@ -580,8 +594,9 @@ static autosage_status_t exec_softmax(autosage_ctx* h, const SoftmaxArgs& a, int
             STAGE(h, "hub_partition", st, launch_hub_partition(a.rows, a.rowptr, hub_t, hub_chunk, meta, st));
         }
     }
-    STAGE(h, "softmax_rows", st, launch_softmax_rows(a, hub_t, wpg, st));
-    if (hub_t > 0) STAGE(h, "softmax_hub", st, launch_softmax_hub(a, hub_chunk, meta, part, st));
+    const int group = softmax_group(h, a.rows.count, nnz, a.H);
+    STAGE(h, "softmax_rows", st, launch_softmax_rows(a, hub_t, wpg, group, st));
+    if (hub_t > 0) STAGE(h, "softmax_hub", st, launch_softmax_hub(a, hub_chunk, group, meta, part, st));
     return AUTOSAGE_OK;
 }
 
@@ -945,7 +960,8 @@ static autosage_status_t exec_attention_backward(autosage_ctx* h, const AttnBwdC
         ba.dS = D;
         ba.H = H;
         ba.scale = c.scale;
-        STAGE(h, "attn_bwd_softmax", st, launch_softmax_bwd(ba, rs.hub_t, rs.hub_chunk, rs.hub_t > 0 ? &meta : nullptr, part, st));
+        STAGE(h, "attn_bwd_softmax", st, launch_softmax_bwd(ba, rs.hub_t, rs.hub_chunk, softmax_group(h, ba.rows.count, nnz, ba.H),
+                                                                rs.hub_t > 0 ? &meta : nullptr, part, st));
     }
     rc = spmm(c.rowptr, c.colind, D, c.K, c.dt, rp, c.dQ);
     if (rc != AUTOSAGE_OK) return rc;
@@ -1151,7 +1167,8 @@ extern "C" autosage_status_t autosage_csr_row_softmax_backward(autosage_handle_t
             return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
         STAGE(h, "hub_partition", st, launch_hub_partition(a.rows, rowptr, hub_t, chunk, meta, st));
     }
-    STAGE(h, "softmax_bwd", st, launch_softmax_bwd(a, hub_t, chunk, hub_t > 0 ? &meta : nullptr, part, st));
+    STAGE(h, "softmax_bwd", st, launch_softmax_bwd(a, hub_t, chunk, softmax_group(h, a.rows.count, nnz, a.H),
+                                                           hub_t > 0 ? &meta : nullptr, part, st));
     return AUTOSAGE_OK;
 }
 

@@ -69,6 +69,8 @@ struct Params {
     int force_ftile = 0;
     int force_wpb = 0;
     int force_hub_t = -1;     // -1 = not forced, 0 = forced off
+    // row-softmax: lanes per light row (0 = from the mean row length, < 0 = one wavefront per row)
+    int softmax_group = 0;
 };
 
 }  // namespace autosage

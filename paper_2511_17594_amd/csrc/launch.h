@@ -145,8 +145,9 @@ struct SoftmaxBwdArgs {
 };
 
 // dS = P * (dP - rowsum(P * dP)); hub rows (degree >= hub_t) through per-chunk partial dots in `part` ([cap_chunks, H]).
-hipError_t launch_softmax_bwd(const SoftmaxBwdArgs& a, int32_t hub_t, int32_t hub_chunk, const HubMeta* meta, float* part,
-                              hipStream_t stream);
+// group: lanes per light row for power-of-two head counts (see launch_softmax_rows).
+hipError_t launch_softmax_bwd(const SoftmaxBwdArgs& a, int32_t hub_t, int32_t hub_chunk, int32_t group, const HubMeta* meta,
+                              float* part, hipStream_t stream);
 
 // CSR transpose: stable sort of the nonzeros by column + index kernels.
 size_t transpose_sort_temp_bytes(int64_t nnz, int64_t n_cols);
@@ -169,8 +170,12 @@ hipError_t launch_sddmm_rows(const SddmmArgs& a, const Resolved& r, hipStream_t 
 hipError_t launch_sddmm_hub(const SddmmArgs& a, const Resolved& r, const HubMeta& meta, hipStream_t stream);
 
 // Row-softmax: light rows, and hub rows through per-chunk (max, sum) partials in `part` ([cap_chunks, H, 2]).
-hipError_t launch_softmax_rows(const SoftmaxArgs& a, int32_t hub_t, int32_t wpg, hipStream_t stream);
-hipError_t launch_softmax_hub(const SoftmaxArgs& a, int32_t hub_chunk, const HubMeta& meta, float* part, hipStream_t stream);
+// group > 0: lanes per row (rounded up to a power of two, at least the lanes one entry takes) of the kernels
+// that put several rows on a wavefront; they need a power-of-two H <= 256 and arrays aligned to min(H, 4)
+// floats, otherwise (and for group <= 0) one wavefront of `wpg` per workgroup takes one row.
+hipError_t launch_softmax_rows(const SoftmaxArgs& a, int32_t hub_t, int32_t wpg, int32_t group, hipStream_t stream);
+hipError_t launch_softmax_hub(const SoftmaxArgs& a, int32_t hub_chunk, int32_t group, const HubMeta& meta, float* part,
+                              hipStream_t stream);
 
 // Degree features: hist[33] (int64), max_deg, nnz and the 1024 rowptr samples, written to `dev_out`
 // (int64[33 + 2 + 1024]); the caller copies it back.

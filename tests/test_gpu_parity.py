@@ -199,6 +199,59 @@ def test_row_softmax(torch, handle, ab, skew_graph, H, hub_t):
     assert np.array_equal(d_s.cpu().numpy(), got)
 
 
+@pytest.mark.parametrize("H,group,hub_t", [
+    (1, 1, 0), (1, 4, 128), (1, 64, 0), (2, 2, 64), (2, 16, 0), (4, 1, 0), (4, 8, 256), (8, 2, 0), (8, 16, 128),
+    (8, 64, 1024), (16, 4, 64), (64, 16, 0), (128, 1, 128), (256, 64, 512), (8, -1, 128), (4, 0, 0),
+])
+def test_row_softmax_lane_groups(torch, ab, skew_graph, H, group, hub_t):
+    """Every lane-group size of the row-softmax (several rows per wavefront, rows that fit one wavefront's
+    registers, rows read twice, hub chunks with vector loads) and the one-row-per-wavefront kernels
+    (group < 0), forward and backward, against the oracle; then the same call on arrays that start one
+    float past a 16-byte boundary, which must fall back to scalar loads and give the same result."""
+    A = skew_graph
+    rng = np.random.default_rng(3100 + H)
+    s = (3.0 * rng.standard_normal((A.nnz, H))).astype(np.float32)
+    s[A.rowptr[11] + 1000:A.rowptr[11] + 1003] = 40.0             # dominant scores in the second chunk of the hub row
+    ref = oracle.row_softmax(A.rowptr, s)
+    dP = rng.standard_normal((A.nnz, H)).astype(np.float32)
+    P32 = ref.astype(np.float32)
+    ref_b = oracle.row_softmax_backward(A.rowptr, P32, dP)
+    mag_b = np.abs(P32.astype(np.float64)) * (np.abs(dP) + np.abs(oracle.row_softmax_backward(A.rowptr, P32, -np.abs(dP))
+                                                                  / np.maximum(ref, 1e-300) + np.abs(dP)))
+    h = ab.Handle(0)
+    try:
+        h.set_param("softmax_group", group)
+        d_rp = dev(A.rowptr, torch)
+        ws = torch.empty(h.workspace_bytes(ab.OP_SOFTMAX, A.n_rows, A.nnz, 1, H, sched_of(ab, hub_t=hub_t)),
+                         dtype=torch.uint8, device="cuda")
+        results = []
+        for shift in (0, 1):                                       # 0: aligned; 1: one float past the alignment
+            pad = torch.zeros(A.nnz * H + 4, device="cuda")
+            d_s, out, d_P, d_dP, dS = (pad.clone() for _ in range(5))
+            view = lambda t: t[shift:shift + A.nnz * H].view(A.nnz, H)
+            view(d_s).copy_(dev(s, torch)); view(d_P).copy_(dev(P32, torch)); view(d_dP).copy_(dev(dP, torch))
+            view(out).fill_(float("nan")); view(dS).fill_(float("nan"))
+            h.csr_row_softmax(A.n_rows, A.nnz, d_rp, view(d_s), view(out), H=H, hub_t=hub_t, workspace=ws)
+            h.csr_row_softmax_backward(A.n_rows, A.nnz, d_rp, view(d_P), view(d_dP), view(dS), H=H, hub_t=hub_t, workspace=ws)
+            torch.cuda.synchronize()
+            got, got_b = view(out).cpu().numpy(), view(dS).cpu().numpy()
+            assert np.isfinite(got).all() and np.isfinite(got_b).all()
+            assert float(out[:shift].abs().sum() + out[shift + A.nnz * H:].abs().sum()) == 0.0     # nothing outside
+            assert float(dS[:shift].abs().sum() + dS[shift + A.nnz * H:].abs().sum()) == 0.0
+            for hh in range(0, H, max(1, H // 8)):
+                assert rel_l1_segments(got[:, hh], ref[:, hh], A.rowptr).max() <= TOL_F32, (H, group, shift, hh)
+                assert rel_l1_segments(got_b[:, hh], ref_b[:, hh], A.rowptr, mag_b[:, hh]).max() <= TOL_F32, (H, group, shift, hh)
+            # in place
+            h.csr_row_softmax(A.n_rows, A.nnz, d_rp, view(d_s), view(d_s), H=H, hub_t=hub_t, workspace=ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(view(d_s).cpu().numpy(), got)
+            results.append(got)
+        if H == 1 or group < 0:
+            assert np.array_equal(results[0], results[1])          # scalar loads either way: same kernel, same bits
+    finally:
+        h.close()
+
+
 @pytest.mark.parametrize("H,d,dtype,qk_std,hub_t", [
     (8, 64, "bf16", None, 256), (8, 64, "bf16", 1.0, 0), (2, 32, "bf16", 1.0, 128), (1, 128, "bf16", 1.0, 64),
     (3, 16, "bf16", 2.0, 512), (4, 16, "f32", 1.0, 256), (8, 64, "f32", 1.0, 0), (16, 8, "bf16", 1.0, 256),
