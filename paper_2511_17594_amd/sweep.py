@@ -7,6 +7,8 @@ For every width: the selector's choice (cold call, then steady state from its ca
 once per nonzero; `--dtype bf16` / `f16` halve the bytes of a gathered row) and its fraction of the
 8 TB/s HBM peak, the rate in compulsory bytes (every array touched exactly once), and the guardrail's
 fallback kernel on the same input.  `--vendor` adds the vendor SpMM reached through torch.sparse.mm.
+`--softmax` prints the row-softmax table instead (forward and backward, H = 1 and 8, over split
+thresholds): 8 bytes per score forward (read + write), 12 backward (P, dP read, dS written).
 Workloads: config1..4 (the benchmark configurations), er (Erdos-Renyi N = 200000, p = 2e-5, the shape of
 the paper's extreme-sparsity stressor) and hubsplit_5k / hubsplit_12k (N = 20000, a few rows of degree
 5000 / 12000, the rest 64 / 32: the shape of the paper's split-versus-baseline table; the number of hub
@@ -55,6 +57,7 @@ def main(argv=None):
     ap.add_argument("--vendor", action="store_true")
     ap.add_argument("--no-sddmm", action="store_true")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16", "f16"], help="element type of the dense input operands")
+    ap.add_argument("--softmax", action="store_true", help="row-softmax forward / backward table instead of SpMM / SDDMM")
     args = ap.parse_args(argv)
 
     import torch
@@ -91,6 +94,30 @@ def main(argv=None):
         m = {0: "plain", 1: "wave-row", 2: "multi-row"}[c["mapping"]]
         return "%s v%d u%d hub %d%s%s" % (m, c["vec_bytes"], c["unroll"], c["hub_t"],
                                           " tile %d" % c["f_tile"] if c["f_tile"] else "", " xcd" if c["xcd_remap"] else "")
+
+    if args.softmax:
+        print("| H | split threshold | forward ms | GB/s | of 8 TB/s | backward ms | GB/s | of 8 TB/s |")
+        print("|---|---|---|---|---|---|---|---|")
+        for H in (1, 8):
+            g = torch.Generator(device="cuda").manual_seed(H)
+            s_in = 3.0 * torch.randn((nnz, H), device="cuda", generator=g)
+            P = torch.empty_like(s_in)
+            dP = torch.randn((nnz, H), device="cuda", generator=g)
+            dS = torch.empty_like(s_in)
+            for hub_t in (0, 512, 1024, 4096):
+                if hub_t == 0 and deg.max() > 100000:
+                    continue                                    # one wavefront on a row that long takes tens of ms
+                ws = torch.empty(h.workspace_bytes(ab.OP_SOFTMAX, N, nnz, 1, H, ab.Schedule(hub_t=hub_t)), dtype=torch.uint8,
+                                 device="cuda")
+                tf = timed(lambda: h.csr_row_softmax(N, nnz, rp, s_in, P, H, hub_t, 0, workspace=ws, stream=stream), args.iters)
+                tb = timed(lambda: h.csr_row_softmax_backward(N, nnz, rp, P, dP, dS, H, hub_t, 0, workspace=ws, stream=stream),
+                           args.iters)
+                bf, bb = 8.0 * nnz * H + 4 * (N + 1), 12.0 * nnz * H + 4 * (N + 1)
+                print("| %d | %d | %.3f | %.0f | %.0f %% | %.3f | %.0f | %.0f %% |"
+                      % (H, hub_t, tf, bf / tf / 1e6, 100 * bf / tf / 1e6 / HBM_PEAK_GBS, tb, bb / tb / 1e6,
+                         100 * bb / tb / 1e6 / HBM_PEAK_GBS), flush=True)
+        h.close()
+        return
 
     print("| op | F | ms | GFLOP/s | GB/s | of 8 TB/s | compulsory GB/s | fallback ms | speed-up | cold call ms | selector's choice |")
     print("|---|---|---|---|---|---|---|---|---|---|---|")
