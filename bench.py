@@ -225,18 +225,43 @@ def main():
             "fallback %.3f ms" % (f, t_sp, 2.0 * nnz * f / t_sp / 1e6, bg / t_sp / 1e6, 100 * bg / t_sp / 1e6 / HBM_PEAK_GBS,
                                   t_fb, t_sd, 2.0 * nnz * f / t_sd / 1e6, bg / t_sd / 1e6,
                                   100 * bg / t_sd / 1e6 / HBM_PEAK_GBS, t_fd))
+    # what this device's memory system sustains for plain streams (read, copy, in-place update), 1 GiB each
+    n_probe = 1 << 30
+    pa = torch.empty(n_probe, dtype=torch.uint8, device="cuda")
+    pb = torch.empty(n_probe, dtype=torch.uint8, device="cuda")
+    pa.zero_()
+    pb.zero_()
+    psum = torch.empty(h.stream_probe_dst_bytes(), dtype=torch.uint8, device="cuda")
+    measured = {
+        "read_gbs": n_probe / timed(lambda: h.stream_probe(ab.STREAM_READ, pa, psum, n_probe, stream=stream)) / 1e6,
+        "copy_gbs": 2 * n_probe / timed(lambda: h.stream_probe(ab.STREAM_COPY, pa, pb, n_probe, stream=stream)) / 1e6,
+        "inplace_gbs": 2 * n_probe / timed(lambda: h.stream_probe(ab.STREAM_INPLACE, None, pb, n_probe, stream=stream)) / 1e6,
+        "bytes": n_probe,
+    }
+    del pa, pb, psum
+    roofline["measured_stream"] = measured
+    roofline["frac_of_measured_read"] = roofline["achieved"] / measured["read_gbs"]
+    log("plain streams over 1 GiB: read %.0f GB/s, copy %.0f GB/s (read + written), in place %.0f GB/s; dominant kernel at "
+        "%.0f%% of the measured read rate" % (measured["read_gbs"], measured["copy_gbs"], measured["inplace_gbs"],
+                                              100 * roofline["frac_of_measured_read"]))
     t_attn = timed(lambda: h.csr_attention(N, rp, ci, dQ, dK, dV, O, H, d, scale, workspace=ws, stream=stream))
     detail["attention_ms"] = t_attn
     log("csr_attention H=%d d=%d bf16: %.3f ms/call" % (H, d, t_attn))
     if not args.no_sweep:
-        try:                                  # the vendor library through PyTorch, as a reported reference only
-            Asp = torch.sparse_csr_tensor(rp.to(torch.int64), ci.to(torch.int64), va, size=(N, N))
-            t_v = timed(lambda: torch.sparse.mm(Asp, dB), iters=3)
-            detail["vendor_spmm_F64_ms"] = t_v
-            log("vendor SpMM through torch.sparse.mm at F=64: %.3f ms" % t_v)
-            del Asp
+        try:                                  # the vendor's sparse library on the same buffers, as a reported reference only
+            from paper_2511_17594_amd import vendor
+            vs = vendor.Session(torch)
+            Cv = torch.empty_like(C)
+            t_algs = vs.spmm_times(N, N, rp, ci, va, dB, Cv, iters=3)
+            t_vsd = vs.sddmm_time(N, N, rp, ci, dX, dB, torch.empty_like(out), iters=3)
+            vs.close()
+            detail["hipsparse_spmm_F64_ms"] = t_algs
+            detail["hipsparse_sddmm_F64_ms"] = t_vsd
+            log("hipSPARSE at F=64: SpMM %s ms, SDDMM %s ms"
+                % ({k: round(v, 3) for k, v in t_algs.items()}, "n/a" if t_vsd is None else "%.3f" % t_vsd))
+            del Cv
         except Exception as e:                # pragma: no cover
-            log("vendor SpMM unavailable: %r" % (e,))
+            log("hipSPARSE unavailable: %r" % (e,))
 
     # CPU baseline: the oracle as it stands, on the host cores, same step
     cpu = None

@@ -332,6 +332,19 @@ autosage_status_t autosage_csr_attention_backward(autosage_handle_t h, int64_t N
 autosage_status_t autosage_profile_begin(autosage_handle_t h);
 autosage_status_t autosage_profile_read(autosage_handle_t h, char* json_buf, size_t n);
 
+/* Bandwidth probe (Experimental setup: rates are judged against what the device sustains).  Launches one
+ * plain streaming kernel over n_bytes (a multiple of 16, both pointers 16-byte aligned, dev) on `stream`:
+ *   AUTOSAGE_STREAM_READ     src is read once; dst receives one fp32 partial sum per workgroup and must hold
+ *                            autosage_stream_probe_dst_bytes() bytes (their total is the sum of src as fp32)
+ *   AUTOSAGE_STREAM_COPY     dst[0 .. n_bytes) = src[0 .. n_bytes)  (n_bytes read + n_bytes written)
+ *   AUTOSAGE_STREAM_INPLACE  dst[i] = 0.5 * dst[i] over n_bytes of fp32 (src unused, may be NULL)
+ * n_bytes = 0 is valid (src may then be NULL).  The caller times it (HIP events, median of repeats);
+ * nothing is allocated, nothing synchronises. */
+typedef enum { AUTOSAGE_STREAM_READ = 0, AUTOSAGE_STREAM_COPY = 1, AUTOSAGE_STREAM_INPLACE = 2 } autosage_stream_mode_t;
+autosage_status_t autosage_stream_probe(autosage_handle_t h, autosage_stream_mode_t mode, const void* src, void* dst,
+                                        size_t n_bytes, void* stream);
+autosage_status_t autosage_stream_probe_dst_bytes(autosage_handle_t h, size_t* bytes);
+
 /* The baseline (fallback) schedule of the guardrail: plain one-wavefront-per-row kernel. */
 autosage_status_t autosage_baseline_schedule(autosage_schedule_t* out);
 

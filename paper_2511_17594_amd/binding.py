@@ -80,6 +80,8 @@ def _load():
         "autosage_csr_attention_backward_workspace_bytes": [vp, i64, i64, i32, i32, i32, i32, c.POINTER(sz)],
         "autosage_csr_attention_backward": [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32,
                                             c.c_float, c.c_int, i32, i32, vp, sz, vp],
+        "autosage_stream_probe": [vp, c.c_int, vp, vp, sz, vp],
+        "autosage_stream_probe_dst_bytes": [vp, c.POINTER(sz)],
         "autosage_profile_begin": [vp],
         "autosage_profile_read": [vp, c.c_char_p, sz],
     }
@@ -93,6 +95,9 @@ def _load():
 
 
 _lib, EXPORTED = _load()
+
+
+STREAM_READ, STREAM_COPY, STREAM_INPLACE = 0, 1, 2
 
 
 def status_string(status: int) -> str:
@@ -318,6 +323,15 @@ class Handle:
         buf = ctypes.create_string_buffer(1 << 16)
         _check(_lib.autosage_last_decision(self._h, buf, len(buf)), "autosage_last_decision")
         return json.loads(buf.value.decode())
+
+    def stream_probe_dst_bytes(self) -> int:
+        out = ctypes.c_size_t()
+        _check(_lib.autosage_stream_probe_dst_bytes(self._h, ctypes.byref(out)), "autosage_stream_probe_dst_bytes")
+        return int(out.value)
+
+    def stream_probe(self, mode: int, src, dst, n_bytes: int, stream=None):
+        """One launch of the plain streaming kernel `mode` (STREAM_READ / STREAM_COPY / STREAM_INPLACE) over n_bytes."""
+        _check(_lib.autosage_stream_probe(self._h, mode, _ptr(src), _ptr(dst), n_bytes, _stream(stream)), "autosage_stream_probe")
 
     def profile_begin(self):
         _check(_lib.autosage_profile_begin(self._h), "autosage_profile_begin")

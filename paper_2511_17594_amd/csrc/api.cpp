@@ -1094,6 +1094,34 @@ extern "C" autosage_status_t autosage_narrow_indices(autosage_handle_t h, int64_
 }
 
 // ------------------------------------------------------------------------------------------
+// bandwidth probe
+// ------------------------------------------------------------------------------------------
+extern "C" autosage_status_t autosage_stream_probe_dst_bytes(autosage_handle_t h, size_t* bytes)
+{
+    if (!h || !bytes) return AUTOSAGE_ERR_INVALID_ARG;
+    *bytes = sizeof(float) * (size_t)stream_probe_blocks(h->cu_count);
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_stream_probe(autosage_handle_t h, autosage_stream_mode_t mode, const void* src,
+                                                   void* dst, size_t n_bytes, void* stream)
+{
+    if (!h) return AUTOSAGE_ERR_INVALID_ARG;
+    if (mode != AUTOSAGE_STREAM_READ && mode != AUTOSAGE_STREAM_COPY && mode != AUTOSAGE_STREAM_INPLACE)
+        return AUTOSAGE_ERR_INVALID_ARG;
+    // zero bytes: nothing to read; the read mode still writes its (zero) partial sums
+    if ((!dst && (n_bytes > 0 || mode == AUTOSAGE_STREAM_READ)) || (mode != AUTOSAGE_STREAM_INPLACE && !src && n_bytes > 0))
+        return AUTOSAGE_ERR_INVALID_ARG;
+    if (n_bytes % 16 != 0 || n_bytes > (size_t(1) << 40)) return AUTOSAGE_ERR_INVALID_ARG;
+    if (((reinterpret_cast<uint64_t>(src) | reinterpret_cast<uint64_t>(dst)) & 15u) != 0) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    if (n_bytes == 0 && mode != AUTOSAGE_STREAM_READ) return AUTOSAGE_OK;
+    HIP_TRY(launch_stream_probe((int)mode, stream_probe_blocks(h->cu_count), src, dst, (int64_t)(n_bytes / 16),
+                                static_cast<hipStream_t>(stream)));
+    return AUTOSAGE_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // telemetry
 // ------------------------------------------------------------------------------------------
 extern "C" autosage_status_t autosage_profile_begin(autosage_handle_t h)

@@ -108,6 +108,49 @@ template <int VEC> __device__ __forceinline__ void store_f32(float* p, const flo
     }
 }
 
+// Streaming accesses: data that is touched once (index arrays, scores, outputs) is loaded and stored
+// with the non-temporal hint, so that it passes through the caches without displacing the gathered
+// dense rows that are reused.  Plain streams measure about 10 % faster with the hint on this chip.
+typedef float stream_f2 __attribute__((ext_vector_type(2)));
+typedef float stream_f4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int stream_load(const int* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ float stream_load(const float* p) { return __builtin_nontemporal_load(p); }
+
+// Loads VEC consecutive floats (p is VEC*4-byte aligned; VEC = 1, 2 or 4).
+template <int VEC> __device__ __forceinline__ void stream_load_f32(const float* p, float* v)
+{
+    if constexpr (VEC == 1) {
+        v[0] = __builtin_nontemporal_load(p);
+    } else if constexpr (VEC == 2) {
+        const stream_f2 t = __builtin_nontemporal_load(reinterpret_cast<const stream_f2*>(p));
+        v[0] = t.x; v[1] = t.y;
+    } else {
+        static_assert(VEC == 4, "unsupported vector width");
+        const stream_f4 t = __builtin_nontemporal_load(reinterpret_cast<const stream_f4*>(p));
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    }
+}
+
+// Stores VEC consecutive fp32 values (p is min(VEC, 4)*4-byte aligned; VEC = 8 is two 16-byte pieces).
+template <int VEC> __device__ __forceinline__ void stream_store_f32(float* p, const float* v)
+{
+    if constexpr (VEC == 1) {
+        __builtin_nontemporal_store(v[0], p);
+    } else if constexpr (VEC == 2) {
+        const stream_f2 t = {v[0], v[1]};
+        __builtin_nontemporal_store(t, reinterpret_cast<stream_f2*>(p));
+    } else if constexpr (VEC == 4) {
+        const stream_f4 t = {v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(t, reinterpret_cast<stream_f4*>(p));
+    } else {
+        static_assert(VEC == 8, "unsupported vector width");
+        const stream_f4 t = {v[0], v[1], v[2], v[3]}, u = {v[4], v[5], v[6], v[7]};
+        __builtin_nontemporal_store(t, reinterpret_cast<stream_f4*>(p));
+        __builtin_nontemporal_store(u, reinterpret_cast<stream_f4*>(p + 4));
+    }
+}
+
 // Value of x held by lane `src` (0..63).  `src` may differ between lanes.
 __device__ __forceinline__ int lane_get(int x, int src) { return __shfl(x, src, kWave); }
 __device__ __forceinline__ float lane_get(float x, int src) { return __shfl(x, src, kWave); }

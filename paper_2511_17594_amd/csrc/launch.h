@@ -186,4 +186,9 @@ hipError_t launch_narrow_indices(int64_t n, const int64_t* src, int32_t* dst, in
 hipError_t launch_validate_csr(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
                                const int32_t* colind, int32_t* dev_flag, hipStream_t stream);
 
+// Streaming kernels for the bandwidth probe: mode 0 = read src (one partial sum per workgroup into dst, `blocks`
+// floats), 1 = copy src to dst, 2 = scale dst in place; n_vec 16-byte vectors.
+int stream_probe_blocks(int cu_count);
+hipError_t launch_stream_probe(int mode, int blocks, const void* src, void* dst, int64_t n_vec, hipStream_t stream);
+
 }  // namespace autosage

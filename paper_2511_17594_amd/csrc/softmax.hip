@@ -421,6 +421,23 @@ __global__ void __launch_bounds__(1024) softmax_bwd_hub_apply_kernel(SoftmaxBwdD
 // shares those heads with the lanes j +- hs, j +- 2 hs, ... of its group.  Rows of at most G * R / hs
 // entries are read once into registers, 64 / G rows per wavefront; each longer row is then taken by
 // the whole wavefront (a group of 64 lanes), so that one long row does not leave the other groups idle.
+// Scores that are read once and every result are moved with streaming (non-temporal) accesses; the first
+// of two reads of a long row or a hub chunk is an ordinary load, so that the second finds it in the cache.
+// Scores that are read once, and every result: streaming accesses when a lane moves 16 bytes.  With narrower
+// vectors (H < 4) neighbouring rows share cache lines across lane groups and wavefronts, and the hint makes
+// those lines be fetched again (measured: 20-45 % slower at H = 1), so they stay ordinary accesses.
+template <int VEC> __device__ __forceinline__ void load_once(const float* p, float* v)
+{
+    if constexpr (VEC == 4) stream_load_f32<4>(p, v);
+    else VecIO<float, VEC>::load(p, v);
+}
+
+template <int VEC> __device__ __forceinline__ void store_result(float* p, const float* v)
+{
+    if constexpr (VEC == 4) stream_store_f32<4>(p, v);
+    else store_f32<VEC>(p, v);
+}
+
 template <int G> __device__ __forceinline__ float heads_max(float x, int hs)
 {
     for (int off = hs; off < G; off <<= 1) x = fmaxf(x, __shfl_xor(x, off, kWave));
@@ -469,7 +486,7 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
         for (int k = 0; k < R; ++k) {
             const int v = k * G + j;
             if (v < nv) {
-                VecIO<float, VEC>::load(a.in + base + (int64_t)v * VEC, s[k]);
+                load_once<VEC>(a.in + base + (int64_t)v * VEC, s[k]);
             } else {
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) s[k][c] = -INFINITY;
@@ -496,7 +513,7 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
             if (v < nv) {
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) s[k][c] *= inv[c];
-                store_f32<VEC>(a.out + base + (int64_t)v * VEC, s[k]);
+                store_result<VEC>(a.out + base + (int64_t)v * VEC, s[k]);
             }
         }
     }
@@ -514,7 +531,7 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
             for (int k = 0; k < R; ++k) {
                 const int64_t v = k * kWave + lane;
                 if (v < nv) {
-                    VecIO<float, VEC>::load(a.in + base + v * VEC, s[k]);
+                    load_once<VEC>(a.in + base + v * VEC, s[k]);
                 } else {
 #pragma unroll
                     for (int c = 0; c < VEC; ++c) s[k][c] = -INFINITY;
@@ -541,7 +558,7 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
                 if (v < nv) {
 #pragma unroll
                     for (int c = 0; c < VEC; ++c) s[k][c] *= inv[c];
-                    store_f32<VEC>(a.out + base + v * VEC, s[k]);
+                    store_result<VEC>(a.out + base + v * VEC, s[k]);
                 }
             }
             continue;
@@ -588,7 +605,7 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
 #pragma unroll
             for (int k = 0; k < R; ++k) {
                 const int64_t v = v0 + k * kWave + lane;
-                if (v < nv) VecIO<float, VEC>::load(a.in + base + v * VEC, s[k]);
+                if (v < nv) load_once<VEC>(a.in + base + v * VEC, s[k]);
             }
 #pragma unroll
             for (int k = 0; k < R; ++k) {
@@ -596,7 +613,7 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
                 if (v < nv) {
 #pragma unroll
                     for (int c = 0; c < VEC; ++c) s[k][c] = __expf(s[k][c] - mx[c]) * inv[c];
-                    store_f32<VEC>(a.out + base + v * VEC, s[k]);
+                    store_result<VEC>(a.out + base + v * VEC, s[k]);
                 }
             }
         }
@@ -621,8 +638,8 @@ __global__ void __launch_bounds__(256) softmax_bwd_groups_kernel(SoftmaxBwdDev a
         for (int k = 0; k < R; ++k) {
             const int v = k * G + j;
             if (v < nv) {
-                VecIO<float, VEC>::load(a.P + base + (int64_t)v * VEC, P[k]);
-                VecIO<float, VEC>::load(a.dP + base + (int64_t)v * VEC, dP[k]);
+                load_once<VEC>(a.P + base + (int64_t)v * VEC, P[k]);
+                load_once<VEC>(a.dP + base + (int64_t)v * VEC, dP[k]);
             } else {
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) P[k][c] = dP[k][c] = 0.f;
@@ -642,7 +659,7 @@ __global__ void __launch_bounds__(256) softmax_bwd_groups_kernel(SoftmaxBwdDev a
             if (v < nv) {
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) P[k][c] = a.scale * (P[k][c] * (dP[k][c] - dot[c]));
-                store_f32<VEC>(a.dS + base + (int64_t)v * VEC, P[k]);
+                store_result<VEC>(a.dS + base + (int64_t)v * VEC, P[k]);
             }
         }
     }
@@ -659,8 +676,8 @@ __global__ void __launch_bounds__(256) softmax_bwd_groups_kernel(SoftmaxBwdDev a
             for (int k = 0; k < R; ++k) {
                 const int64_t v = k * kWave + lane;
                 if (v < nv) {
-                    VecIO<float, VEC>::load(a.P + base + v * VEC, P[k]);
-                    VecIO<float, VEC>::load(a.dP + base + v * VEC, dP[k]);
+                    load_once<VEC>(a.P + base + v * VEC, P[k]);
+                    load_once<VEC>(a.dP + base + v * VEC, dP[k]);
                 } else {
 #pragma unroll
                     for (int c = 0; c < VEC; ++c) P[k][c] = dP[k][c] = 0.f;
@@ -680,7 +697,7 @@ __global__ void __launch_bounds__(256) softmax_bwd_groups_kernel(SoftmaxBwdDev a
                 if (v < nv) {
 #pragma unroll
                     for (int c = 0; c < VEC; ++c) P[k][c] = a.scale * (P[k][c] * (dP[k][c] - dot[c]));
-                    store_f32<VEC>(a.dS + base + v * VEC, P[k]);
+                    store_result<VEC>(a.dS + base + v * VEC, P[k]);
                 }
             }
             continue;
@@ -715,8 +732,8 @@ __global__ void __launch_bounds__(256) softmax_bwd_groups_kernel(SoftmaxBwdDev a
             for (int k = 0; k < R; ++k) {
                 const int64_t v = v0 + k * kWave + lane;
                 if (v < nv) {
-                    VecIO<float, VEC>::load(a.P + base + v * VEC, P[k]);
-                    VecIO<float, VEC>::load(a.dP + base + v * VEC, dP[k]);
+                    load_once<VEC>(a.P + base + v * VEC, P[k]);
+                    load_once<VEC>(a.dP + base + v * VEC, dP[k]);
                 }
             }
 #pragma unroll
@@ -725,7 +742,7 @@ __global__ void __launch_bounds__(256) softmax_bwd_groups_kernel(SoftmaxBwdDev a
                 if (v < nv) {
 #pragma unroll
                     for (int c = 0; c < VEC; ++c) P[k][c] = a.scale * (P[k][c] * (dP[k][c] - dot[c]));
-                    store_f32<VEC>(a.dS + base + v * VEC, P[k]);
+                    store_result<VEC>(a.dS + base + v * VEC, P[k]);
                 }
             }
         }
@@ -840,7 +857,7 @@ __global__ void __launch_bounds__(kHubLanes) softmax_hub_normalise_vec_kernel(So
 #pragma unroll
         for (int k = 0; k < kHubR; ++k) {
             const int64_t v = v0 + k * kHubLanes + threadIdx.x;
-            if (v < sp.nv) VecIO<float, VEC>::load(a.in + sp.base + v * VEC, s[k]);
+            if (v < sp.nv) load_once<VEC>(a.in + sp.base + v * VEC, s[k]);
         }
 #pragma unroll
         for (int k = 0; k < kHubR; ++k) {
@@ -848,7 +865,7 @@ __global__ void __launch_bounds__(kHubLanes) softmax_hub_normalise_vec_kernel(So
             if (v < sp.nv) {
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) s[k][c] = __expf(s[k][c] - mx[c]) * inv[c];
-                store_f32<VEC>(a.out + sp.base + v * VEC, s[k]);
+                store_result<VEC>(a.out + sp.base + v * VEC, s[k]);
             }
         }
     }
@@ -915,8 +932,8 @@ __global__ void __launch_bounds__(kHubLanes) softmax_bwd_hub_apply_vec_kernel(So
         for (int k = 0; k < kHubR; ++k) {
             const int64_t v = v0 + k * kHubLanes + threadIdx.x;
             if (v < sp.nv) {
-                VecIO<float, VEC>::load(a.P + sp.base + v * VEC, P[k]);
-                VecIO<float, VEC>::load(a.dP + sp.base + v * VEC, dP[k]);
+                load_once<VEC>(a.P + sp.base + v * VEC, P[k]);
+                load_once<VEC>(a.dP + sp.base + v * VEC, dP[k]);
             }
         }
 #pragma unroll
@@ -925,7 +942,7 @@ __global__ void __launch_bounds__(kHubLanes) softmax_bwd_hub_apply_vec_kernel(So
             if (v < sp.nv) {
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) P[k][c] = a.scale * (P[k][c] * (dP[k][c] - dot[c]));
-                store_f32<VEC>(a.dS + sp.base + v * VEC, P[k]);
+                store_result<VEC>(a.dS + sp.base + v * VEC, P[k]);
             }
         }
     }

@@ -6,7 +6,8 @@ For every width: the selector's choice (cold call, then steady state from its ca
 `--iters` HIP-event timings), GFLOP/s = 2*nnz*F/t, algorithmic GB/s (every gathered dense row counted
 once per nonzero; `--dtype bf16` / `f16` halve the bytes of a gathered row) and its fraction of the
 8 TB/s HBM peak, the rate in compulsory bytes (every array touched exactly once), and the guardrail's
-fallback kernel on the same input.  `--vendor` adds the vendor SpMM reached through torch.sparse.mm.
+fallback kernel on the same input.  `--vendor` adds hipSPARSE on the same buffers (its fastest CSR SpMM
+algorithm and its SDDMM, called directly through `vendor.py`).
 `--softmax` prints the row-softmax table instead (forward and backward, H = 1 and 8, over split
 thresholds): 8 bytes per score forward (read + write), 12 backward (P, dP read, dS written).
 Workloads: config1..4 (the benchmark configurations), er (Erdos-Renyi N = 200000, p = 2e-5, the shape of
@@ -155,14 +156,20 @@ def main(argv=None):
                      tb, tb / t, cold, short(choice)), flush=True)
         if args.vendor and args.dtype == "f32":
             try:
-                Asp = torch.sparse_csr_tensor(rp.to(torch.int64), ci.to(torch.int64), va, size=(N, M))
-                tv = timed(lambda: torch.sparse.mm(Asp, B), 3)
-                print("| vendor SpMM (torch.sparse.mm) | %d | %.3f | %.0f | %.0f | %.0f %% | %.0f | | | | |"
-                      % (F, tv, 2.0 * nnz * F / tv / 1e6, bg / tv / 1e6, 100 * bg / tv / 1e6 / HBM_PEAK_GBS,
-                         bmin["SpMM"] / tv / 1e6), flush=True)
-                del Asp
+                from . import vendor
+                vs = vendor.Session(torch)
+                algs = vs.spmm_times(N, M, rp, ci, va, B, C, iters=3)
+                tsd = vs.sddmm_time(N, M, rp, ci, X, B, out, iters=3)
+                vs.close()
+                rows = [("hipSPARSE SpMM (%s)" % min(algs, key=algs.get), min(algs.values()), "SpMM")] if algs else []
+                if tsd is not None:
+                    rows.append(("hipSPARSE SDDMM", tsd, "SDDMM"))
+                for label, tv, kind in rows:
+                    print("| %s | %d | %.3f | %.0f | %.0f | %.0f %% | %.0f | | | | |"
+                          % (label, F, tv, 2.0 * nnz * F / tv / 1e6, bg / tv / 1e6, 100 * bg / tv / 1e6 / HBM_PEAK_GBS,
+                             bmin[kind] / tv / 1e6), flush=True)
             except Exception as e:                      # pragma: no cover
-                print("vendor SpMM unavailable: %r" % (e,), file=sys.stderr)
+                print("hipSPARSE unavailable: %r" % (e,), file=sys.stderr)
         del B, X, C, out, ws
     h.close()
 
