@@ -104,7 +104,9 @@ autosage_status_t autosage_destroy(autosage_handle_t h);
 const char* autosage_status_string(autosage_status_t s);
 
 /* Sets a parameter by name.  Selector: "alpha", "probe_frac", "probe_iters", "probe_cap_ms",
- * "probe_topk", "probe_min_rows", "replay_only", "confirm_full", "memoize_signature".
+ * "probe_topk", "probe_min_rows", "replay_only", "confirm_full", "memoize_signature", "baseline_bound"
+ * (1, default: the guardrail's baseline is first bounded from below by timing it without its rows of
+ * 1024 entries or more, and timed whole only when that bound does not decide; 0: always timed whole).
  * Row-softmax (forward and backward): "softmax_group" = lanes that share one light row (rounded up to
  * a power of two <= 64, at least the lanes one entry of H heads takes); 0 (default) derives it from
  * the mean row length, a negative value keeps one wavefront per row.

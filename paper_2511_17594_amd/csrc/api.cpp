@@ -263,6 +263,12 @@ autosage_status_t exec_spmm(autosage_ctx* h, const SpmmArgs& a, const Resolved& 
                             hipStream_t st)
 {
     if (a.rows.count == 0) return AUTOSAGE_OK;
+    if (h->probe_skip_deg > 0) {                // lower bound of a schedule: its light rows only
+        Resolved light = r;
+        light.hub_t = h->probe_skip_deg;
+        STAGE(h, "spmm_rows", st, launch_spmm_rows(a, light, st));
+        return AUTOSAGE_OK;
+    }
     HubMeta meta{};
     float* part = nullptr;
     if (r.hub_t > 0) {
@@ -279,6 +285,12 @@ autosage_status_t exec_sddmm(autosage_ctx* h, const SddmmArgs& a, const Resolved
                              hipStream_t st)
 {
     if (a.rows.count == 0) return AUTOSAGE_OK;
+    if (h->probe_skip_deg > 0 && r.tiles <= 1) {
+        Resolved light = r;
+        light.hub_t = h->probe_skip_deg;
+        STAGE(h, "sddmm_rows", st, launch_sddmm_rows(a, light, st));
+        return AUTOSAGE_OK;
+    }
     HubMeta meta{};
     if (r.hub_t > 0) {
         if (!carve_hub(ws, ws_bytes, a.rows.count, nnz, r.hub_t, r.hub_chunk, 0, &meta, nullptr, nullptr))
@@ -433,6 +445,7 @@ static bool param_access(Params& p, const char* name, double* value, bool set)
     P_INT("replay_only", replay_only)
     P_INT("confirm_full", confirm_full)
     P_INT("memoize_signature", memoize_signature)
+    P_INT("baseline_bound", baseline_bound)
     P_INT("force_ftile", force_ftile)
     P_INT("force_wpb", force_wpb)
     P_INT("force_hub_t", force_hub_t)
@@ -706,9 +719,13 @@ autosage_status_t exec_attention(autosage_ctx* h, const AttnCall& c, const autos
     char* hub_ws = static_cast<char*>(workspace) + score_bytes;
     const size_t hub_ws_bytes = workspace_bytes - score_bytes;
 
+    if (h->probe_skip_deg > 0) {                // lower bound of the three stages: light rows only, no hub kernels
+        rs.hub_t = rp.hub_t = h->probe_skip_deg;
+    }
+    const bool light_only = h->probe_skip_deg > 0;
     HubMeta meta{};
     float* part = nullptr;
-    if (rs.hub_t > 0) {
+    if (rs.hub_t > 0 && !light_only) {
         if (!carve_hub(hub_ws, hub_ws_bytes, rows.count, nnz, rs.hub_t, rs.hub_chunk, (int64_t)attention_part_floats(H, d),
                        &meta, &part, nullptr))
             return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
@@ -730,7 +747,7 @@ autosage_status_t exec_attention(autosage_ctx* h, const AttnCall& c, const autos
     sa.scale = c.scale;
     if (nnz > 0) {
         STAGE(h, "attn_sddmm_rows", st, launch_sddmm_rows(sa, rs, st));
-        if (rs.hub_t > 0) STAGE(h, "attn_sddmm_hub", st, launch_sddmm_hub(sa, rs, meta, st));
+        if (rs.hub_t > 0 && !light_only) STAGE(h, "attn_sddmm_hub", st, launch_sddmm_hub(sa, rs, meta, st));
     }
     // stage 2: row-softmax in place
     SoftmaxArgs ma{};
@@ -739,8 +756,12 @@ autosage_status_t exec_attention(autosage_ctx* h, const AttnCall& c, const autos
     ma.in = S;
     ma.out = S;
     ma.H = H;
-    rc = exec_softmax(h, ma, nnz, rs.hub_t, rs.hub_chunk, rs.wpg, rs.hub_t > 0 ? &meta : nullptr, part, nullptr, 0, st);
-    if (rc != AUTOSAGE_OK) return rc;
+    if (light_only) {
+        STAGE(h, "softmax_rows", st, launch_softmax_rows(ma, rs.hub_t, rs.wpg, softmax_group(h, ma.rows.count, nnz, H), st));
+    } else {
+        rc = exec_softmax(h, ma, nnz, rs.hub_t, rs.hub_chunk, rs.wpg, rs.hub_t > 0 ? &meta : nullptr, part, nullptr, 0, st);
+        if (rc != AUTOSAGE_OK) return rc;
+    }
     // stage 3: weighted sum of V rows with per-head weights
     SpmmArgs pa{};
     pa.rows = rows;
@@ -756,7 +777,7 @@ autosage_status_t exec_attention(autosage_ctx* h, const AttnCall& c, const autos
     pa.heads = H > 1 ? H : 1;
     pa.head_dim = d;
     STAGE(h, "attn_spmm_rows", st, launch_spmm_rows(pa, rp, st));
-    if (rp.hub_t > 0) STAGE(h, "attn_spmm_hub", st, launch_spmm_hub(pa, rp, meta, part, st));
+    if (rp.hub_t > 0 && !light_only) STAGE(h, "attn_spmm_hub", st, launch_spmm_hub(pa, rp, meta, part, st));
     return AUTOSAGE_OK;
 }
 

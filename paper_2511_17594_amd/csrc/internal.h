@@ -65,6 +65,7 @@ struct Params {
     int replay_only = 0;
     int confirm_full = 1;
     int memoize_signature = 1;
+    int baseline_bound = 1;   // 1: time the baseline's light rows first and the whole baseline only when that bound does not decide
     // forced knobs from the environment (0 = not forced)
     int force_ftile = 0;
     int force_wpb = 0;
@@ -96,6 +97,9 @@ struct autosage_ctx {
     };
     std::vector<StageSpan> spans;
     size_t spans_used = 0;
+    // > 0 while the selector times a lower bound of the baseline: the row kernels of the next launches skip
+    // rows of at least this many entries and no hub kernel runs (outputs of skipped rows stay untouched)
+    int probe_skip_deg = 0;
 };
 
 namespace autosage {
@@ -105,6 +109,7 @@ constexpr int kMinHubT = 64;               // smallest split threshold the libra
 // workgroup's stride past the end of a row: both limits together keep every such sum below 2^31.
 constexpr int kMaxHubChunk = 1 << 20;                                  // longest chunk of a split row
 constexpr int64_t kMaxNnz = (int64_t(1) << 31) - (int64_t(1) << 20);   // most nonzeros, and most rows, of a call
+constexpr int kBaselineBoundDeg = 1024;     // rows this long are left out when the selector bounds the baseline from below
 constexpr int kSelectorMinHubT = 512;      // smallest threshold the selector proposes for SpMM / SDDMM
 constexpr int kSelectorMinChunk = 256;     // shortest hub chunk the selector proposes
 constexpr double kTileOperandBytes = 96.0 * 1024 * 1024;   // dense operands above this get narrow-tile candidates

@@ -418,18 +418,21 @@ autosage_status_t run_once(autosage_ctx* h, const OpInput& in, const RowMap& row
 }
 
 // Median of up to `iters` timed runs after one warm-up run; stops early once the timed runs add up
-// to cap_ms.  The warm-up is timed as well: when it alone takes four caps or more (a slow schedule
-// on this input) it is returned as the measurement, since cold-start effects are negligible at that
-// length and repeating it would only burn time.  Returns +inf when the schedule cannot run; `why`
+// to cap_ms.  The warm-up is timed as well.  The first launch of a kernel also pays for loading its code
+// object (milliseconds), so a long warm-up alone says nothing: it is repeated once, and only when the
+// repeat too takes four caps or more (a schedule that is slow on this input) is that time returned as the
+// measurement instead of burning more repeats (first_launch = false: the kernels have run before, a long
+// warm-up is returned at once).  Returns +inf when the schedule cannot run; `why`
 // (optional) then holds the status of the run that failed.
 double time_schedule(autosage_ctx* h, const OpInput& in, const RowMap& rows, const autosage_schedule_t& s, void* ws,
-                     size_t ws_bytes, hipStream_t st, int iters, double cap_ms, autosage_status_t* why = nullptr)
+                     size_t ws_bytes, hipStream_t st, int iters, double cap_ms, autosage_status_t* why = nullptr,
+                     bool first_launch = true)
 {
     const double inf = std::numeric_limits<double>::infinity();
     std::vector<double> t;
     double total = 0.0;
     if (why) *why = AUTOSAGE_ERR_HIP;
-    for (int i = -1; i < iters; ++i) {
+    for (int i = -2; i < iters; ++i) {
         if (hipEventRecord(h->ev0, st) != hipSuccess) return inf;
         const autosage_status_t rc = run_once(h, in, rows, s, ws, ws_bytes, st);
         if (rc != AUTOSAGE_OK) {
@@ -440,7 +443,12 @@ double time_schedule(autosage_ctx* h, const OpInput& in, const RowMap& rows, con
         if (hipEventSynchronize(h->ev1) != hipSuccess) return inf;
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, h->ev0, h->ev1) != hipSuccess) return inf;
-        if (i < 0) {                                  // warm-up
+        if (i == -2) {                                // warm-up (may include the code object load)
+            if (ms >= 4.0 * cap_ms && !first_launch) return ms;
+            if (ms < 4.0 * cap_ms) ++i;               // short: no second warm-up
+            continue;
+        }
+        if (i == -1) {                                // repeat of a long warm-up
             if (ms >= 4.0 * cap_ms) return ms;
             continue;
         }
@@ -637,14 +645,29 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
         }
     }
 
+    // The baseline walks every row with one wavefront, so a single row of tens of thousands of entries makes
+    // one run of it take many milliseconds.  When such rows exist the baseline is first bounded from below:
+    // it is timed on the sample with the rows of kBaselineBoundDeg entries or more left out.  The full
+    // baseline cannot be faster than that, so a candidate accepted against the bound (t* <= alpha * bound)
+    // is accepted against the baseline itself; only when the bound does not settle the decision is the whole
+    // baseline timed.  `light` runs the baseline in that mode; the probe calls pass `why` and may be the first
+    // launch of the baseline's kernels, the confirmation calls are not.
+    auto time_baseline = [&](const RowMap& rows, bool light, int iters, double cap, autosage_status_t* why,
+                             int skip_deg = kBaselineBoundDeg) {
+        h->probe_skip_deg = light ? skip_deg : 0;
+        const double t = time_schedule(h, in, rows, base, workspace, workspace_bytes, st, iters, cap, why, why != nullptr);
+        h->probe_skip_deg = 0;
+        return t;
+    };
+    const bool can_bound = h->params.baseline_bound != 0 && max_deg >= kBaselineBoundDeg;
     // the baseline must be able to run on this input: report its own error (e.g. a short workspace)
     autosage_status_t base_rc = AUTOSAGE_OK;
-    const double tb = time_schedule(h, in, sample, base, workspace, workspace_bytes, st, h->params.probe_iters,
-                                    h->params.probe_cap_ms, &base_rc);
+    double tb = time_baseline(sample, can_bound, h->params.probe_iters, h->params.probe_cap_ms, &base_rc);
     if (!std::isfinite(tb)) return base_rc;
+    bool tb_is_bound = can_bound;
     std::vector<double> tc(topk);
     js << ",\"cache_hit\":false,\"replay_miss\":false,\"probe_rows\":" << sample.count << ",\"probe_stride\":" << stride
-       << ",\"t_baseline_ms\":" << num(tb) << ",\"candidates\":[";
+       << ",\"candidates\":[";
     for (int c = 0; c < topk; ++c) {
         tc[c] = time_schedule(h, in, sample, cands[c], workspace, workspace_bytes, st, h->params.probe_iters,
                               h->params.probe_cap_ms);
@@ -655,22 +678,35 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
 
     // 5. guardrail
     int choice = decide_from_times(topk, tc.data(), tb, h->params.alpha);
+    if (choice < 0 && tb_is_bound) {              // the bound rejects everything: ask the baseline itself
+        tb = time_baseline(sample, false, h->params.probe_iters, h->params.probe_cap_ms, &base_rc);
+        if (!std::isfinite(tb)) return base_rc;
+        tb_is_bound = false;
+        choice = decide_from_times(topk, tc.data(), tb, h->params.alpha);
+    }
     double t_choice = choice >= 0 ? tc[choice] : tb;
-    js << ",\"choice_index\":" << choice;
+    js << ",\"t_baseline_ms\":" << num(tb) << ",\"baseline_light_rows_only\":" << (tb_is_bound ? "true" : "false")
+       << ",\"choice_index\":" << choice;
 
     // 6. the guardrail speaks about the sample; confirm once on the whole input
     if (choice >= 0 && h->params.confirm_full) {
         const RowMap full{0, 1, (int32_t)n_rows, 0};
         const double cap = std::numeric_limits<double>::infinity();
         const double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, cap);
-        // The sample is a subset of the rows, so the baseline needs at least its sample time on the whole
-        // input: when that bound already covers the choice's full-input time the baseline is not run again.
-        // Otherwise a baseline run that takes more than twice the choice settles the question in one run.
-        const bool bound_settles = sample.count < n_rows && tb >= tf_c;
-        const double tf_b = bound_settles ? tb : time_schedule(h, in, full, base, workspace, workspace_bytes, st, 2, 0.5 * tf_c);
+        // Lower bounds of the baseline on the whole input, cheapest first: its time on the sample (a subset of
+        // the rows), then its rows below 8 * kBaselineBoundDeg entries on the whole input (the longest of them
+        // still costs one wavefront well under a millisecond).  When a bound already covers the choice's time the
+        // baseline itself is not run; otherwise one run of it that takes more than twice the choice settles it.
+        bool bound_settles = sample.count < n_rows && tb >= tf_c;
+        double tf_b = tb;
+        if (!bound_settles && can_bound) {
+            tf_b = time_baseline(full, true, 2, 0.5 * tf_c, nullptr, 8 * kBaselineBoundDeg);
+            bound_settles = std::isfinite(tf_b) && tf_b >= tf_c;
+        }
+        if (!bound_settles) tf_b = time_baseline(full, false, 2, 0.5 * tf_c, nullptr);
         const bool demote = !(tf_c <= tf_b);
         js << ",\"confirm\":{\"t_choice_ms\":" << num(tf_c) << ",\"t_baseline_ms\":" << num(tf_b)
-           << ",\"baseline_bound_from_sample\":" << (bound_settles ? "true" : "false") << ",\"demoted\":"
+           << ",\"baseline_bound_only\":" << (bound_settles ? "true" : "false") << ",\"demoted\":"
            << (demote ? "true" : "false") << "}";
         if (demote) {
             choice = -1;
