@@ -198,3 +198,35 @@ def test_replayed_decision_falls_back_when_alignment_changes(torch, ab, graph):
     ref_abs = oracle.spmm(A.rowptr, A.colind, np.abs(A.val), np.abs(B))
     assert rel_l1_rows(C2.cpu().numpy(), ref, ref_abs).max() <= 1e-5
     h.close()
+
+
+@pytest.mark.parametrize("op_name", ["spmm", "sddmm"])
+def test_baseline_light_row_bound_is_below_the_baseline_and_decides_alike(torch, ab, graph, op_name):
+    """The selector's cheap baseline time (rows of >= 1024 entries left out) is a lower bound of the baseline's
+    time on the same sample, so the rule applied to it (Proposition 1: t* <= alpha * t_b) can only be stricter."""
+    A, F = graph, 64
+    assert A.degrees.max() >= 1024
+    B, X = ops(torch, ab, A, F)
+    rp, ci, va, dB, dX = (dev(t, torch) for t in (A.rowptr, A.colind, A.val, B, X))
+    C = torch.empty((A.n_rows, F), dtype=torch.float32, device="cuda")
+    out = torch.empty(A.nnz, dtype=torch.float32, device="cuda")
+    logs = {}
+    for bound in (1, 0):
+        h = ab.Handle(0)
+        h.set_param("baseline_bound", bound)
+        ws = torch.empty(h.workspace_bytes(ab.OP_SPMM, A.n_rows, A.nnz, F), dtype=torch.uint8, device="cuda")
+        if op_name == "spmm":
+            h.decide(ab.OP_SPMM, A.n_rows, A.n_cols, rp, ci, va, dB, None, C, F, workspace=ws)
+        else:
+            h.decide(ab.OP_SDDMM, A.n_rows, A.n_cols, rp, ci, None, dX, dB, out, F, workspace=ws)
+        d = h.last_decision()
+        h.close()
+        t = [c["t_ms"] if c["t_ms"] is not None else float("inf") for c in d["candidates"]]
+        assert d["choice_index"] == oracle.decide(t, d["t_baseline_ms"], d["alpha"])
+        logs[bound] = d
+    assert logs[1]["baseline_light_rows_only"] is True and logs[0]["baseline_light_rows_only"] is False
+    # the bound leaves the longest rows out: it is the smaller time (generous margin for timer noise)
+    assert logs[1]["t_baseline_ms"] <= 1.25 * logs[0]["t_baseline_ms"]
+    # accepted against the bound => accepted against the whole baseline
+    if logs[1]["choice_index"] >= 0:
+        assert min(c["t_ms"] for c in logs[1]["candidates"]) <= logs[1]["alpha"] * 1.25 * logs[0]["t_baseline_ms"]
