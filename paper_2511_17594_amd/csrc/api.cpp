@@ -285,7 +285,7 @@ autosage_status_t exec_sddmm(autosage_ctx* h, const SddmmArgs& a, const Resolved
                              hipStream_t st)
 {
     if (a.rows.count == 0) return AUTOSAGE_OK;
-    if (h->probe_skip_deg > 0 && r.tiles <= 1) {
+    if (h->probe_skip_deg > 0 && (r.tiles <= 1 || r.mapping == MAP_PLAIN)) {
         Resolved light = r;
         light.hub_t = h->probe_skip_deg;
         STAGE(h, "sddmm_rows", st, launch_sddmm_rows(a, light, st));
