@@ -438,6 +438,12 @@ template <int VEC> __device__ __forceinline__ void store_result(float* p, const 
     else store_f32<VEC>(p, v);
 }
 
+// exp(x - m) with m given pre-multiplied by log2(e): one fused multiply-add and one v_exp_f32 per element.
+constexpr float kLog2e = 1.4426950408889634f;
+__device__ __forceinline__ float exp_minus(float x, float m_log2e) { return __builtin_amdgcn_exp2f(fmaf(x, kLog2e, -m_log2e)); }
+// 1 / x to one unit in the last place (v_rcp_f32) instead of the ten-instruction IEEE division.
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
 template <int G> __device__ __forceinline__ float heads_max(float x, int hs)
 {
     for (int off = hs; off < G; off <<= 1) x = fmaxf(x, __shfl_xor(x, off, kWave));
@@ -499,13 +505,14 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
 #pragma unroll
             for (int k = 1; k < R; ++k) m = fmaxf(m, s[k][c]);
             m = heads_max<G>(m, hs);
+            const float m2 = m * kLog2e;
             float l = 0.f;
 #pragma unroll
             for (int k = 0; k < R; ++k) {
-                s[k][c] = __expf(s[k][c] - m);                  // exp(-inf) = 0 for the padding
+                s[k][c] = exp_minus(s[k][c], m2);                // exp(-inf) = 0 for the padding
                 l += s[k][c];
             }
-            inv[c] = 1.f / heads_sum<G>(l, hs);
+            inv[c] = fast_rcp(heads_sum<G>(l, hs));
         }
 #pragma unroll
         for (int k = 0; k < R; ++k) {
@@ -544,13 +551,14 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
 #pragma unroll
                 for (int k = 1; k < R; ++k) m = fmaxf(m, s[k][c]);
                 m = heads_max<kWave>(m, hs);
+                const float m2 = m * kLog2e;
                 float l = 0.f;
 #pragma unroll
                 for (int k = 0; k < R; ++k) {
-                    s[k][c] = __expf(s[k][c] - m);
+                    s[k][c] = exp_minus(s[k][c], m2);
                     l += s[k][c];
                 }
-                inv[c] = 1.f / heads_sum<kWave>(l, hs);
+                inv[c] = fast_rcp(heads_sum<kWave>(l, hs));
             }
 #pragma unroll
             for (int k = 0; k < R; ++k) {
@@ -588,8 +596,9 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
                     acc[c].m = m;
                 }
                 if (acc[c].m > -INFINITY) {
+                    const float am2 = acc[c].m * kLog2e;
 #pragma unroll
-                    for (int k = 0; k < R; ++k) acc[c].l += __expf(s[k][c] - acc[c].m);
+                    for (int k = 0; k < R; ++k) acc[c].l += exp_minus(s[k][c], am2);
                 }
             }
         }
@@ -597,8 +606,8 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
             const MaxSum t = ms_wave_merge(acc[c], hs);
-            mx[c] = t.m;
-            inv[c] = 1.f / t.l;
+            mx[c] = t.m * kLog2e;
+            inv[c] = fast_rcp(t.l);
         }
         for (int64_t v0 = 0; v0 < nv; v0 += kWave * R) {
             float s[R][VEC];
@@ -612,7 +621,7 @@ __global__ void __launch_bounds__(256) softmax_groups_kernel(SoftmaxDev a)
                 const int64_t v = v0 + k * kWave + lane;
                 if (v < nv) {
 #pragma unroll
-                    for (int c = 0; c < VEC; ++c) s[k][c] = __expf(s[k][c] - mx[c]) * inv[c];
+                    for (int c = 0; c < VEC; ++c) s[k][c] = exp_minus(s[k][c], mx[c]) * inv[c];
                     store_result<VEC>(a.out + base + v * VEC, s[k]);
                 }
             }
@@ -812,8 +821,9 @@ __global__ void __launch_bounds__(kHubLanes) softmax_hub_partial_vec_kernel(Soft
                 acc[c].m = m;
             }
             if (acc[c].m > -INFINITY) {
+                const float am2 = acc[c].m * kLog2e;
 #pragma unroll
-                for (int k = 0; k < kHubR; ++k) acc[c].l += __expf(s[k][c] - acc[c].m);
+                for (int k = 0; k < kHubR; ++k) acc[c].l += exp_minus(s[k][c], am2);
             }
         }
     }
@@ -849,8 +859,8 @@ __global__ void __launch_bounds__(kHubLanes) softmax_hub_normalise_vec_kernel(So
     float mx[VEC], inv[VEC];
 #pragma unroll
     for (int c = 0; c < VEC; ++c) {                                // row total, left by the merge kernel
-        mx[c] = a.part[((int64_t)sp.c0 * a.H + h0 + c) * 2 + 0];
-        inv[c] = 1.f / a.part[((int64_t)sp.c0 * a.H + h0 + c) * 2 + 1];
+        mx[c] = a.part[((int64_t)sp.c0 * a.H + h0 + c) * 2 + 0] * kLog2e;
+        inv[c] = fast_rcp(a.part[((int64_t)sp.c0 * a.H + h0 + c) * 2 + 1]);
     }
     for (int64_t v0 = 0; v0 < sp.nv; v0 += kHubLanes * kHubR) {
         float s[kHubR][VEC];
@@ -864,7 +874,7 @@ __global__ void __launch_bounds__(kHubLanes) softmax_hub_normalise_vec_kernel(So
             const int64_t v = v0 + k * kHubLanes + threadIdx.x;
             if (v < sp.nv) {
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) s[k][c] = __expf(s[k][c] - mx[c]) * inv[c];
+                for (int c = 0; c < VEC; ++c) s[k][c] = exp_minus(s[k][c], mx[c]) * inv[c];
                 store_result<VEC>(a.out + sp.base + v * VEC, s[k]);
             }
         }
