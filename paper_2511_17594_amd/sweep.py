@@ -8,7 +8,10 @@ once per nonzero; `--dtype bf16` / `f16` halve the bytes of a gathered row) and 
 8 TB/s HBM peak, the rate in compulsory bytes (every array touched exactly once), and the guardrail's
 fallback kernel on the same input.  `--vendor` adds hipSPARSE on the same buffers (its fastest CSR SpMM
 algorithm and its SDDMM, called directly through `vendor.py`).
-`--softmax` prints the row-softmax table instead (forward and backward, H = 1 and 8, over split
+`--attention` prints the CSR-attention table instead (H = 8, d = 64, 16-bit operands from `--dtype`, default
+bf16): the selector's choice, the single pass and the three-stage pipeline at fixed split thresholds, and
+the backward call; bytes are the algorithmic ones (a K and a V row per nonzero, plus 16 bytes per score and
+head for the three stages).  `--softmax` prints the row-softmax table instead (forward and backward, H = 1 and 8, over split
 thresholds): 8 bytes per score forward (read + write), 12 backward (P, dP read, dS written).
 Workloads: config1..4 (the benchmark configurations), er (Erdos-Renyi N = 200000, p = 2e-5, the shape of
 the paper's extreme-sparsity stressor) and hubsplit_5k / hubsplit_12k (N = 20000, a few rows of degree
@@ -59,6 +62,7 @@ def main(argv=None):
     ap.add_argument("--no-sddmm", action="store_true")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16", "f16"], help="element type of the dense input operands")
     ap.add_argument("--softmax", action="store_true", help="row-softmax forward / backward table instead of SpMM / SDDMM")
+    ap.add_argument("--attention", action="store_true", help="CSR attention (forward and backward) table instead of SpMM / SDDMM")
     args = ap.parse_args(argv)
 
     import torch
@@ -95,6 +99,65 @@ def main(argv=None):
         m = {0: "plain", 1: "wave-row", 2: "multi-row"}[c["mapping"]]
         return "%s v%d u%d hub %d%s%s" % (m, c["vec_bytes"], c["unroll"], c["hub_t"],
                                           " tile %d" % c["f_tile"] if c["f_tile"] else "", " xcd" if c["xcd_remap"] else "")
+
+    if args.attention:
+        if N != M:
+            raise SystemExit("attention needs a square pattern")
+        H, d = 8, 64
+        half = {"f32": torch.bfloat16, "bf16": torch.bfloat16, "f16": torch.float16}[args.dtype]
+        in_dt = ab.F16 if args.dtype == "f16" else ab.BF16
+        g = torch.Generator(device="cuda").manual_seed(5)
+        Q, K, V = (torch.randn((N, H, d), device="cuda", generator=g).mul_(d ** -0.25).to(half) for _ in range(3))
+        O = torch.empty((N, H, d), device="cuda")
+        scale = d ** -0.5
+        HD, e = H * d, 2
+        b_fused = 4 * (N + 1) + 4 * nnz + 2.0 * nnz * HD * e + N * HD * e + N * HD * 4
+        b_three = b_fused + 16.0 * nnz * H + 8 * (N + 1) + 8 * nnz
+        ws = torch.empty(h.workspace_bytes(ab.OP_ATTENTION, N, nnz, d, H), dtype=torch.uint8, device="cuda")
+        print("| pipeline | split threshold | ms | GFLOP/s (4·nnz·H·d) | algorithmic GB | GB/s | of 8 TB/s |")
+        print("|---|---|---|---|---|---|---|")
+
+        def row(label, hub_t, t, nbytes):
+            print("| %s | %s | %.3f | %.0f | %.2f | %.0f | %.0f %% |" % (label, hub_t, t, 4.0 * nnz * HD / t / 1e6, nbytes / 1e9,
+                                                                nbytes / t / 1e6, 100 * nbytes / t / 1e6 / HBM_PEAK_GBS), flush=True)
+
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        h.csr_attention(N, rp, ci, Q, K, V, O, H, d, scale, in_dt=in_dt, workspace=ws, stream=stream)
+        torch.cuda.synchronize()
+        cold = (time.perf_counter() - t0) * 1e3
+        ch = h.last_decision().get("choice")
+        t = timed(lambda: h.csr_attention(N, rp, ci, Q, K, V, O, H, d, scale, in_dt=in_dt, workspace=ws, stream=stream), args.iters)
+        fused = ch["mapping"] == ab.MAP_FUSED
+        row("selector's choice (%s, cold call %.0f ms)" % ("single pass" if fused else "three stages", cold), ch["hub_t"], t,
+            b_fused if fused else b_three)
+        thresholds = [256, 1024] if deg.max() >= 4096 else [0, 1024]
+        for mapping, label, nbytes in ((ab.MAP_FUSED, "single pass", b_fused), (ab.MAP_WAVE_ROW, "three stages", b_three)):
+            for hub_t in thresholds:
+                sc = ab.Schedule(mapping=mapping, waves_per_wg=4, hub_t=hub_t, hub_chunk=4 * hub_t if mapping == ab.MAP_FUSED else 0)
+                wsx = torch.empty(h.workspace_bytes(ab.OP_ATTENTION, N, nnz, d, H, sc), dtype=torch.uint8, device="cuda")
+                fn = lambda: h.csr_attention(N, rp, ci, Q, K, V, O, H, d, scale, in_dt=in_dt, sched=sc, workspace=wsx, stream=stream)
+                row(label, hub_t, timed(fn, args.iters), nbytes)
+                del wsx
+        # backward: the chain rule through the three stages on the pattern and on its transpose
+        t_rp = torch.empty(N + 1, dtype=torch.int32, device="cuda")
+        t_ci = torch.empty(nnz, dtype=torch.int32, device="cuda")
+        perm = torch.empty(nnz, dtype=torch.int32, device="cuda")
+        wst = torch.empty(h.csr_transpose_workspace_bytes(N, N, nnz), dtype=torch.uint8, device="cuda")
+        h.csr_transpose(N, N, nnz, rp, ci, None, t_rp, t_ci, None, perm, wst, stream=stream)
+        del wst
+        dO = torch.randn((N, H, d), device="cuda", generator=g)
+        dQ, dK, dV = (torch.empty((N, H, d), device="cuda") for _ in range(3))
+        hub_b = 512 if deg.max() >= 4096 else 0
+        wsb = torch.empty(h.csr_attention_backward_workspace_bytes(N, nnz, H, d, hub_b), dtype=torch.uint8, device="cuda")
+        tb = timed(lambda: h.csr_attention_backward(N, rp, ci, t_rp, t_ci, perm, Q, K, V, dO, dQ, dK, dV, H, d, scale, in_dt=in_dt,
+                                                    hub_t=hub_b, workspace=wsb, stream=stream, nnz=nnz), max(3, args.iters // 2))
+        # gathered rows: K twice and V once (16-bit), Q once (16-bit), dO once (fp32); scores: about 14 passes of [nnz, H] fp32
+        b_bwd = nnz * HD * (4.0 * e + 4.0) + 14.0 * 4 * nnz * H + 5.0 * N * HD * 4
+        print("| backward | %d | %.3f | %.0f | %.2f | %.0f | %.0f %% |" % (hub_b, tb, 10.0 * nnz * HD / tb / 1e6, b_bwd / 1e9, b_bwd / tb / 1e6,
+                                                                      100 * b_bwd / tb / 1e6 / HBM_PEAK_GBS), flush=True)
+        h.close()
+        return
 
     if args.softmax:
         print("| H | split threshold | forward ms | GB/s | of 8 TB/s | backward ms | GB/s | of 8 TB/s |")
