@@ -625,6 +625,18 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
                 }
             }
         }
+        // attention: both pipelines are probed; when the single pass fills the k above, the best-ranked
+        // three-stage candidate is added (which of the two wins depends on how much of K and V the caches keep)
+        if (op == AUTOSAGE_OP_ATTENTION) {
+            bool have_three = false;
+            for (const autosage_schedule_t& c : cands) have_three = have_three || c.mapping == AUTOSAGE_MAP_WAVE_ROW;
+            for (size_t i = 0; i < all.size() && !have_three; ++i) {
+                if (all[i].mapping != AUTOSAGE_MAP_WAVE_ROW) continue;
+                cands.push_back(all[i]);
+                est.push_back(all_est[i]);
+                have_three = true;
+            }
+        }
     }
     const int topk = (int)cands.size();
 

@@ -156,7 +156,7 @@ def test_attention_decision(torch, ab, graph):
     d1 = h.last_decision()
     assert d1["cache_hit"] is False and d1["op"] == ab.OP_ATTENTION and d1["H"] == H and d1["F"] == d
     kinds = {c["sched"]["mapping"] for c in d1["candidates"]}
-    assert ab.MAP_FUSED in kinds                                     # the single pass is among the probed candidates
+    assert ab.MAP_FUSED in kinds and ab.MAP_WAVE_ROW in kinds        # both pipelines are among the probed candidates
     t = [c["t_ms"] if c["t_ms"] is not None else float("inf") for c in d1["candidates"]]
     assert d1["choice_index"] == oracle.decide(t, d1["t_baseline_ms"], d1["alpha"])
     assert s1.mapping in (ab.MAP_FUSED, ab.MAP_WAVE_ROW) and s1.hub_t > 0     # 8192-long rows: never the unsplit baseline
