@@ -263,6 +263,21 @@ def main():
         except Exception as e:                # pragma: no cover
             log("hipSPARSE unavailable: %r" % (e,))
 
+    # the same cold calls on a fresh handle (empty cache) now that the kernels' code objects are loaded: what a
+    # long-running process pays when it meets a new graph
+    h2 = ab.Handle(0)
+    cold_loaded = {}
+    for name, fn in (("spmm", lambda: h2.spmm(N, N, rp, ci, va, dB, C, F, workspace=ws, stream=stream)),
+                     ("sddmm", lambda: h2.sddmm(N, N, rp, ci, dX, dY, out, F, workspace=ws, stream=stream)),
+                     ("attention", lambda: h2.csr_attention(N, rp, ci, dQ, dK, dV, O, H, d, scale, workspace=ws, stream=stream))):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        cold_loaded[name] = (time.perf_counter() - t0) * 1e3
+    h2.close()
+    log("cold calls with the code objects loaded: %s" % {k: round(v, 2) for k, v in cold_loaded.items()})
+
     # CPU baseline: the oracle as it stands, on the host cores, same step
     cpu = None
     if not args.no_cpu:
@@ -296,7 +311,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "selector": {"spmm": dec_spmm.get("choice"), "sddmm": dec_sddmm.get("choice"), "attention": dec_attn.get("choice"),
-                     "cold_call_ms": {"spmm": cold_spmm_ms, "sddmm": cold_sddmm_ms, "attention": cold_attn_ms}},
+                     "cold_call_ms": {"spmm": cold_spmm_ms, "sddmm": cold_sddmm_ms, "attention": cold_attn_ms},
+                     "cold_call_code_loaded_ms": cold_loaded},
         "stages": {k: {"avg_ms": v["avg_ms"], "gbs": v["gbs"]} for k, v in per_stage.items()},
         "detail": detail,
     }
