@@ -253,7 +253,7 @@ def main():
             vs = vendor.Session(torch)
             Cv = torch.empty_like(C)
             t_algs = vs.spmm_times(N, N, rp, ci, va, dB, Cv, iters=3)
-            t_vsd = vs.sddmm_time(N, N, rp, ci, dX, dB, torch.empty_like(out), iters=3)
+            t_vsd = vs.sddmm_time(N, N, rp, ci, dX, dB, torch.zeros_like(out), iters=3)
             vs.close()
             detail["hipsparse_spmm_F64_ms"] = t_algs
             detail["hipsparse_sddmm_F64_ms"] = t_vsd

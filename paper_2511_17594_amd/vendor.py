@@ -126,7 +126,8 @@ class Session:
         return out
 
     def sddmm_time(self, n_rows, n_cols, rowptr, colind, X, Y, out, iters=5):
-        """ms per call for out[p] = <X[i, :], Y[colind[p], :]> (None when the library refuses the shapes)."""
+        """ms per call for out[p] = <X[i, :], Y[colind[p], :]> (None when the library refuses the shapes).
+        `out` must hold finite values on entry: the library forms beta * out with beta = 0."""
         torch, lib = self.torch, self.lib
         nnz = int(colind.numel())
         c, x, y = self._csr(n_rows, n_cols, nnz, rowptr, colind, out), self._dense(X), self._dense(Y)
