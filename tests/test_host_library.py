@@ -71,6 +71,35 @@ def test_params_and_baseline(ab, host):
             host.set_param(*bad)
     b = ab.baseline_schedule()
     assert b.mapping == ab.MAP_PLAIN and b.hub_t == 0 and b.f_tile == 64
+    # defaults and round trips of the later parameters
+    assert host.get_param("baseline_bound") == 1 and host.get_param("softmax_group") == 0
+    for name, value in (("baseline_bound", 0), ("softmax_group", 16), ("softmax_group", -1)):
+        host.set_param(name, value)
+        assert host.get_param(name) == value
+
+
+def test_stream_probe_argument_checks_need_no_device(ab, host):
+    """The probe's argument checks come before the device check; a host-only handle then refuses the launch."""
+    assert host.stream_probe_dst_bytes() % 4 == 0 and host.stream_probe_dst_bytes() > 0
+    import ctypes
+    buf = (ctypes.c_char * 64)()
+    aligned = (ctypes.addressof(buf) + 15) & ~15
+
+    class FakeTensor:                                   # what the binding needs of a tensor: a pointer
+        def __init__(self, ptr):
+            self._ptr = ptr
+
+        def data_ptr(self):
+            return self._ptr
+
+    good = FakeTensor(aligned)
+    for args, status in (((ab.STREAM_COPY, good, good, 24), ab.ERR_INVALID_ARG),          # not a multiple of 16
+                         ((ab.STREAM_COPY, FakeTensor(aligned + 4), good, 16), ab.ERR_INVALID_ARG),
+                         ((9, good, good, 16), ab.ERR_INVALID_ARG),
+                         ((ab.STREAM_COPY, good, good, 16), ab.ERR_UNSUPPORTED)):          # valid, but no device
+        with pytest.raises(ab.AutosageError) as ei:
+            host.stream_probe(*args, stream=0)
+        assert ei.value.status == status
 
 
 def test_workspace_bytes(ab, host):
