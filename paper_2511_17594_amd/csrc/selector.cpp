@@ -703,8 +703,9 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
     // 6. the guardrail speaks about the sample; confirm once on the whole input
     if (choice >= 0 && h->params.confirm_full) {
         const RowMap full{0, 1, (int32_t)n_rows, 0};
-        const double cap = std::numeric_limits<double>::infinity();
-        const double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, cap);
+        // its kernels have run on the sample: up to two timed runs after a warm-up, fewer once 2.5 ms are spent,
+        // and a warm-up of 10 ms or more is itself the measurement (large inputs: one run)
+        const double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, 2.5, nullptr, false);
         // Lower bounds of the baseline on the whole input, cheapest first: its time on the sample (a subset of
         // the rows), then its rows below 8 * kBaselineBoundDeg entries on the whole input (the longest of them
         // still costs one wavefront well under a millisecond).  When a bound already covers the choice's time the
