@@ -204,3 +204,81 @@ def test_config4_large_sparse_full_size(torch, ab, handle):
     ref_abs = oracle.sddmm(As.rowptr, As.colind, absb(Xs), absb(Bb))
     got = out[torch.from_numpy(idx).cuda()].cpu().numpy()
     assert rel_l1_segments(got, ref, As.rowptr, ref_abs).max() <= 2e-2
+
+
+def rows_only(A, rows):
+    """The N x N pattern of A with every row emptied except `rows` (ascending); (rowptr, colind)."""
+    rp = A.rowptr.astype(np.int64)
+    deg = np.zeros(A.n_rows, dtype=np.int64)
+    deg[rows] = rp[rows + 1] - rp[rows]
+    out_rp = np.zeros(A.n_rows + 1, dtype=np.int64)
+    np.cumsum(deg, out=out_rp[1:])
+    idx = np.concatenate([np.arange(rp[r], rp[r + 1]) for r in rows]) if rows.size else np.zeros(0, np.int64)
+    return out_rp.astype(np.int32), np.ascontiguousarray(A.colind[idx])
+
+
+def test_config5_attention_backward_full_size(torch, ab, handle, config2):
+    """Adjoint of the attention of config 5 at full size.  dQ of a row depends on that row only, so sampled rows
+    (the 16 longest among them) are compared with the oracle run on the pattern with all other rows emptied; dK
+    and dV of a column collect from every row that holds it, so sampled columns are compared with the oracle on
+    the pattern restricted to exactly those rows; two identities cover all columns at once: the rows of P sum
+    to 1, hence sum_j dV_j = sum_i dO_i over the non-empty rows, and the rows of dS sum to 0, hence
+    sum_j dK_j = 0."""
+    import scipy.sparse as sp
+    A, H, d = config2, 8, 64
+    N, scale, hub_t = A.n_rows, d ** -0.5, 512
+    Q, K, V = W.config5_attention(N, H, d, seed=0, qk_std=1.0)
+    rng = np.random.default_rng(77)
+    dO = rng.standard_normal((N, H, d), dtype=np.float32)
+    rp, ci, dQm, dKm, dVm, d_dO = (dev(t, torch) for t in (A.rowptr, A.colind, Q, K, V, dO))
+    t_rp = torch.empty(N + 1, dtype=torch.int32, device="cuda")
+    t_ci = torch.empty(A.nnz, dtype=torch.int32, device="cuda")
+    perm = torch.empty(A.nnz, dtype=torch.int32, device="cuda")
+    wst = torch.empty(handle.csr_transpose_workspace_bytes(N, N, A.nnz), dtype=torch.uint8, device="cuda")
+    handle.csr_transpose(N, N, A.nnz, rp, ci, None, t_rp, t_ci, None, perm, wst)
+    del wst
+    gQ, gK, gV = (torch.full((N, H, d), float("nan"), dtype=torch.float32, device="cuda") for _ in range(3))
+    ws = torch.empty(handle.csr_attention_backward_workspace_bytes(N, A.nnz, H, d, hub_t), dtype=torch.uint8, device="cuda")
+    handle.csr_attention_backward(N, rp, ci, t_rp, t_ci, perm, dQm, dKm, dVm, d_dO, gQ, gK, gV, H, d, scale, in_dt=ab.BF16,
+                                  hub_t=hub_t, workspace=ws, nnz=A.nnz)
+    torch.cuda.synchronize()
+    del ws
+    assert bool(torch.isfinite(gQ).all() and torch.isfinite(gK).all() and torch.isfinite(gV).all())
+
+    # dQ on sampled rows (with the longest ones)
+    rows = sample_rows(A, 200, 9)
+    s_rp, s_ci = rows_only(A, rows)
+    print("oracle backward on %d rows, %d nonzeros" % (rows.size, s_ci.size), flush=True)
+    rQ, _, _ = oracle.csr_attention_backward(s_rp, s_ci, Q, K, V, dO, scale)
+    got = gQ[torch.from_numpy(rows).cuda()].cpu().numpy().reshape(rows.size, -1)
+    err = rel_l1_rows(got, rQ[rows].reshape(rows.size, -1))
+    assert err.max() <= 2e-2, ("dQ", float(err.max()), int(rows[err.argmax()]))
+    del rQ
+
+    # dK, dV on sampled columns that no row of 8192 entries or more holds (so that the kept rows stay few and short)
+    M = sp.csr_matrix((np.ones(A.nnz, dtype=np.int8), A.colind, A.rowptr.astype(np.int64)), shape=(N, N))
+    long_rows = np.flatnonzero(A.degrees >= 8192)
+    touched = np.zeros(N, dtype=bool)
+    touched[M[long_rows].indices] = True
+    free_cols = np.flatnonzero(~touched & (np.asarray(M.sum(axis=0)).ravel() > 0))
+    assert free_cols.size >= 50
+    cols = np.sort(rng.choice(free_cols, size=min(100, free_cols.size), replace=False))
+    keep = np.unique(M.tocsc()[:, cols].indices)                   # every row that holds one of the columns
+    k_rp, k_ci = rows_only(A, keep)
+    print("oracle backward on the %d rows that hold %d sampled columns, %d nonzeros" % (keep.size, cols.size, k_ci.size), flush=True)
+    _, rK, rV = oracle.csr_attention_backward(k_rp, k_ci, Q, K, V, dO, scale)
+    sel = torch.from_numpy(cols).cuda()
+    for name, g, r in (("dK", gK, rK), ("dV", gV, rV)):
+        got = g[sel].cpu().numpy().reshape(cols.size, -1)
+        err = rel_l1_rows(got, r[cols].reshape(cols.size, -1))
+        assert err.max() <= 2e-2, (name, float(err.max()), int(cols[err.argmax()]))
+    del rK, rV
+
+    # identities over all columns
+    nonempty = torch.from_numpy(A.degrees > 0).cuda()
+    sum_dO = d_dO[nonempty].double().sum(dim=0)
+    sum_dV = gV.double().sum(dim=0)
+    scale_v = d_dO[nonempty].double().abs().sum(dim=0)
+    assert float(((sum_dV - sum_dO).abs() / scale_v).max()) <= 1e-5
+    sum_dK = gK.double().sum(dim=0)
+    assert float((sum_dK.abs() / gK.double().abs().sum(dim=0)).max()) <= 1e-4
