@@ -95,6 +95,41 @@ def test_config1_tiny_full_compare(torch, ab, handle):
     assert rel_l1_segments(out.cpu().numpy(), ref, A.rowptr, ref_abs).max() <= 1e-5
 
 
+def check_row_softmax(torch, ab, handle, A, d_rowptr, H, hub_t, rows, seed):
+    """Row-softmax of [nnz, H] scores at full size: sampled rows against the oracle, every row and head sums to
+    1, and the backward call on the forward's output against the oracle on the same rows."""
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    s = 3.0 * torch.randn((A.nnz, H), device="cuda", generator=g)
+    dP = torch.randn((A.nnz, H), device="cuda", generator=g)
+    P = torch.full_like(s, float("nan"))
+    dS = torch.full_like(s, float("nan"))
+    ws = torch.empty(handle.workspace_bytes(ab.OP_SOFTMAX, A.n_rows, A.nnz, 1, H, ab.Schedule(hub_t=hub_t)), dtype=torch.uint8,
+                     device="cuda")
+    handle.csr_row_softmax(A.n_rows, A.nnz, d_rowptr, s, P, H, hub_t, 0, workspace=ws)
+    handle.csr_row_softmax_backward(A.n_rows, A.nnz, d_rowptr, P, dP, dS, H, hub_t, 0, workspace=ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(P).all() and torch.isfinite(dS).all())
+    # every non-empty row sums to 1 per head (prefix sums in float64), and the rows of dS sum to 0
+    rp = d_rowptr.long()
+    nonempty = rp[1:] > rp[:-1]
+    for arr, target, tol in ((P, 1.0, 2e-5), (dS, 0.0, 2e-4)):
+        csum = torch.cat([torch.zeros((1, H), dtype=torch.float64, device="cuda"), arr.double().cumsum(dim=0)])
+        sums = (csum[rp[1:]] - csum[rp[:-1]])[nonempty]
+        assert float((sums - target).abs().max()) <= tol, (H, hub_t, target)
+        del csum, sums
+    As = W.row_slice(A, rows)
+    rp64 = A.rowptr.astype(np.int64)
+    idx = torch.from_numpy(np.concatenate([np.arange(rp64[r], rp64[r + 1]) for r in rows])).cuda()
+    s_h, P_h, dP_h, dS_h = (t[idx].cpu().numpy() for t in (s, P, dP, dS))
+    ref = oracle.row_softmax(As.rowptr, s_h)
+    ref_b = oracle.row_softmax_backward(As.rowptr, P_h, dP_h)
+    mag_b = np.abs(P_h.astype(np.float64)) * (np.abs(dP_h) + np.abs(oracle.row_softmax_backward(As.rowptr, P_h, -np.abs(dP_h))
+                                                                    / np.maximum(P_h.astype(np.float64), 1e-300) + np.abs(dP_h)))
+    for h in range(H):
+        assert rel_l1_segments(P_h[:, h], ref[:, h], As.rowptr).max() <= 1e-5, (H, hub_t, h)
+        assert rel_l1_segments(dS_h[:, h], ref_b[:, h], As.rowptr, mag_b[:, h]).max() <= 1e-5, (H, hub_t, h)
+
+
 @pytest.fixture(scope="module")
 def config2():
     A = W.config2_powerlaw()
@@ -125,6 +160,11 @@ def test_config2_powerlaw_full_size(torch, ab, handle, config2, F):
     assert np.array_equal(light_rows.cpu().numpy()[:nl], o_light)
     hist, mx, nnz, sig = handle.graph_features(n, n, d_csr[0])
     assert sig == oracle.graph_signature(A.rowptr, n) and mx == 65536 and nnz == A.nnz
+
+
+@pytest.mark.parametrize("H,hub_t", [(1, 1024), (8, 1024), (8, 4096)])
+def test_row_softmax_full_size_config2(torch, ab, handle, config2, H, hub_t):
+    check_row_softmax(torch, ab, handle, config2, dev(config2.rowptr, torch), H, hub_t, sample_rows(config2, 400, 6), seed=H)
 
 
 def test_config5_attention_full_size(torch, ab, handle, config2):
@@ -204,6 +244,10 @@ def test_config4_large_sparse_full_size(torch, ab, handle):
     ref_abs = oracle.sddmm(As.rowptr, As.colind, absb(Xs), absb(Bb))
     got = out[torch.from_numpy(idx).cuda()].cpu().numpy()
     assert rel_l1_segments(got, ref, As.rowptr, ref_abs).max() <= 2e-2
+    del C, out, ws, dB, dX
+    # row-softmax (forward and backward) on the same pattern: one head and eight
+    check_row_softmax(torch, ab, handle, A, d_csr[0], 1, 4096, rows, seed=41)
+    check_row_softmax(torch, ab, handle, A, d_csr[0], 8, 1024, rows, seed=48)
 
 
 def rows_only(A, rows):
