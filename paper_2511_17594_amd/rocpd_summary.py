@@ -3,6 +3,7 @@
     python -m paper_2511_17594_amd.rocpd_summary kernels  <kernel-trace .db>
     python -m paper_2511_17594_amd.rocpd_summary counters <FETCH_SIZE .db> <WRITE_SIZE .db> [--traffic-out FILE]
     python -m paper_2511_17594_amd.rocpd_summary fetch    <FETCH_SIZE .db>
+    python -m paper_2511_17594_amd.rocpd_summary issue    <SQ counters .db> [--match REGEX]
 
 `kernels` prints calls / total / average duration per kernel from the profiler's per-dispatch begin and
 end times, and the average over the last `--last` dispatches of each kernel: the selector's cold calls
@@ -12,6 +13,10 @@ launch the same kernels on row samples, so only the trailing dispatches are the 
 launch of every kernel (mean over its last `--last` dispatches, the full-input ones), and with
 `--traffic-out` writes the "stage bytes" lines that `bench.py` reports as `roofline.traffic`.
 `fetch` is the read half alone (one profiler run), with the rate each kernel fetched at.
+`issue` reads a run with SQ_WAVES, SQ_INSTS_VALU, SQ_INSTS_SALU, SQ_INSTS_LDS and SQ_INSTS_VMEM_RD and prints the
+instructions per wavefront of every kernel and the share of the kernel's duration that issuing its vector-ALU
+instructions alone takes (4 cycles each on one of the 4 x 256 SIMDs at 2.4 GHz): how far a kernel is from being
+bound by instruction issue rather than by memory.
 Reads only; runs on the CPU.
 """
 from __future__ import annotations
@@ -119,6 +124,37 @@ def fetch_report(fetch_path, last):
     return "\n".join(out)
 
 
+SIMDS, CLOCK_GHZ, VALU_CYCLES = 256 * 4, 2.4, 4
+
+
+def issue_report(path, last, match):
+    agg = counter_samples(path)
+    kernels = sorted({k for k, _ in agg})
+    out = ["Means over the last %d launches of each kernel; VALU issue = SQ_INSTS_VALU x %d cycles / %d SIMDs / (duration x %.1f GHz)."
+           % (last, VALU_CYCLES, SIMDS, CLOCK_GHZ), "",
+           "| kernel | launches | ms | wavefronts | VALU / wave | SALU / wave | LDS / wave | VMEM read / wave | VALU issue |",
+           "|---|---|---|---|---|---|---|---|---|"]
+    for k in kernels:
+        if (match and not re.search(match, k)) or (k, "SQ_WAVES") not in agg:
+            continue
+
+        def mean(counter):
+            tail = agg.get((k, counter), [])[-last:]
+            return sum(v for v, _ in tail) / len(tail) if tail else 0.0
+
+        tail = agg[(k, "SQ_WAVES")][-last:]
+        dur_ns = sum(d for _, d in tail) / len(tail)
+        waves = mean("SQ_WAVES")
+        if waves <= 0 or dur_ns <= 0:
+            continue
+        valu = mean("SQ_INSTS_VALU")
+        out.append("| `%s` | %d | %.4f | %.0f | %.0f | %.0f | %.0f | %.1f | %.0f %% |"
+                   % (k, len(agg[(k, "SQ_WAVES")]), dur_ns / 1e6, waves, valu / waves, mean("SQ_INSTS_SALU") / waves,
+                      mean("SQ_INSTS_LDS") / waves, mean("SQ_INSTS_VMEM_RD") / waves,
+                      100.0 * valu * VALU_CYCLES / SIMDS / (dur_ns * CLOCK_GHZ)))
+    return "\n".join(out)
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -133,7 +169,14 @@ def main(argv=None):
     f = sub.add_parser("fetch")
     f.add_argument("db")
     f.add_argument("--last", type=int, default=5)
+    i = sub.add_parser("issue")
+    i.add_argument("db")
+    i.add_argument("--last", type=int, default=3)
+    i.add_argument("--match", default=None, help="only kernels whose short name matches this regular expression")
     args = ap.parse_args(argv)
+    if args.cmd == "issue":
+        print(issue_report(args.db, args.last, args.match))
+        return
     if args.cmd == "fetch":
         print(fetch_report(args.db, args.last))
         return

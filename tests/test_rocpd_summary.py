@@ -45,3 +45,22 @@ def test_counter_report_scales_by_the_copy_calibration(tmp_path):
     assert "attn_fused_rows" in text and "copyBuffer" not in text.split("|---")[1]
     out = R.fetch_report(pf, last=5)
     assert "8192.0" in out                                   # MB read per launch
+
+
+def test_issue_report_turns_instruction_counts_into_a_share_of_the_duration(tmp_path):
+    k = "void autosage::(anonymous namespace)::softmax_groups_kernel<8, 1, 8>(autosage::(anonymous namespace)::SoftmaxDev)"
+    other = "void autosage::spmm_rows_kernel<float, 4, 16, 1, 4, 1, false>(autosage::SpmmDev)"
+    dur = 1_000_000                                         # 1 ms = 2.4e6 cycles
+    valu = 0.5 * 2.4e6 * 1024 / 4                           # issuing these takes half of the duration on 1024 SIMDs
+    rows = []
+    for i in range(3):
+        rows += [(k, "SQ_WAVES", 1000.0, i, dur), (k, "SQ_INSTS_VALU", valu, i, dur), (k, "SQ_INSTS_SALU", 50_000.0, i, dur),
+                 (k, "SQ_INSTS_LDS", 10_000.0, i, dur), (k, "SQ_INSTS_VMEM_RD", 8_000.0, i, dur)]
+    rows += [(other, "SQ_WAVES", 10.0, 9, dur), (other, "SQ_INSTS_VALU", 100.0, 9, dur)]
+    p = str(tmp_path / "sq.db")
+    make_db(p, [], rows)
+    lines = [l for l in R.issue_report(p, last=3, match="softmax").split("\n") if l.startswith("| `")]
+    assert len(lines) == 1 and "softmax_groups_kernel<8, 1, 8>" in lines[0]
+    c = [x.strip() for x in lines[0].strip("|").split("|")]
+    assert c[1] == "3" and float(c[2]) == 1.0 and float(c[3]) == 1000 and float(c[4]) == round(valu / 1000)
+    assert c[5] == "50" and c[6] == "10" and c[7] == "8.0" and c[8] == "50 %"
