@@ -105,6 +105,7 @@ def test_random_shape_and_schedule(torch, ab, handle, seed):
                 handle.sddmm(A.n_rows, A.n_cols, d_rp, d_ci, d_X, d_B, out, F, dt=dt, sched=s, workspace=ws, nnz=A.nnz)
         except ab.AutosageError as e:
             assert e.status in (ab.ERR_UNSUPPORTED, ab.ERR_INVALID_ARG), tag          # a shape this schedule has no kernel for
+            print("   %s: schedule refused (%s)" % (op, e), flush=True)
             continue
         torch.cuda.synchronize()
         if op == "spmm":
