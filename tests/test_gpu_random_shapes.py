@@ -171,3 +171,41 @@ def test_random_softmax_and_attention(torch, ab, handle, seed):
         got = O.cpu().numpy()
         assert np.isfinite(got).all(), (seed, mapping)
         assert rel_l1_rows(got.reshape(-1, d), ref.reshape(-1, d)).max() <= 2e-2, (seed, mapping)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shape_through_the_selector(torch, ab, seed):
+    """The same random inputs with sched = NULL: whatever the probes make the selector pick must match the oracle,
+    the decision must follow the rule on its own logged times, and a second call must replay it."""
+    rng = np.random.default_rng(9800 + seed)
+    A = random_matrix(rng)
+    F = int(rng.choice(WIDTHS))
+    kind = str(rng.choice(["f32", "bf16", "f16"]))
+    B, absf = operands(rng, A.n_cols, F, kind)
+    X, _ = operands(rng, A.n_rows, F, kind)
+    print((seed, A.n_rows, A.n_cols, A.nnz, F, kind), flush=True)
+    d_rp, d_ci, d_v, d_B, d_X = (dev(t, torch) for t in (A.rowptr, A.colind, A.val, B, X))
+    dt = dtype_code(ab, B)
+    h = ab.Handle(0)
+    try:
+        ws = torch.empty(h.workspace_bytes(ab.OP_SPMM, A.n_rows, A.nnz, F), dtype=torch.uint8, device="cuda")
+        C = torch.full((A.n_rows, F), float("nan"), dtype=torch.float32, device="cuda")
+        out = torch.full((max(A.nnz, 1),), float("nan"), dtype=torch.float32, device="cuda")
+        for op in ("spmm", "sddmm"):
+            for call in range(2):
+                if op == "spmm":
+                    h.spmm(A.n_rows, A.n_cols, d_rp, d_ci, d_v, d_B, C, F, dt=dt, workspace=ws, nnz=A.nnz)
+                else:
+                    h.sddmm(A.n_rows, A.n_cols, d_rp, d_ci, d_X, d_B, out, F, dt=dt, workspace=ws, nnz=A.nnz)
+                d = h.last_decision()
+                assert d["cache_hit"] is (call == 1), (op, call, d)
+                if call == 0:
+                    t = [c["t_ms"] if c["t_ms"] is not None else float("inf") for c in d["candidates"]]
+                    assert d["choice_index"] == oracle.decide(t, d["t_baseline_ms"], d["alpha"]), (op, d)
+            torch.cuda.synchronize()
+        assert rel_l1_rows(C.cpu().numpy(), oracle.spmm(A.rowptr, A.colind, A.val, B),
+                           oracle.spmm(A.rowptr, A.colind, np.abs(A.val), absf(B))).max() <= 1e-5
+        assert rel_l1_segments(out.cpu().numpy()[:A.nnz], oracle.sddmm(A.rowptr, A.colind, X, B), A.rowptr,
+                               oracle.sddmm(A.rowptr, A.colind, absf(X), absf(B))).max() <= 1e-5
+    finally:
+        h.close()
