@@ -1,15 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the CSR SpMM / SDDMM / CSR-attention hot path on one MI355X.
 
-One *step* is one pass of the whole hot path over the power-law skew stressor (N = 262144,
-mean 32 nonzeros per row, hub rows up to 65536): SpMM and SDDMM at F = 64 in fp32 with the
-schedule the selector chose (replayed from its cache; the plan/hub partition runs inside
-every call), and the multi-head CSR attention (H = 8, d = 64, bf16 operands, fp32 scores and
-accumulators; SDDMM -> row-softmax -> SpMM in the pipeline form and hub threshold the selector chose).  All inputs are resident in HBM before the timed region.
+One *step* is one pass of the whole hot path over the largest single-GPU workloads of the evaluation, all
+inputs resident in HBM before the timed region:
 
-Prints one JSON line: whole-step GFLOP/s (2*nnz*F per SpMM/SDDMM, 4*nnz*H*d for attention),
-the roofline of the dominant kernel measured with HIP events inside the timed region, and the
-CPU oracle timed on the host cores as a reported baseline.  Everything else goes to stderr.
+  large sparse graph      (N = 2 449 029, ~126.7 M nonzeros, shaped like the paper's second real graph)
+                          SpMM and SDDMM at F = 128, fp32
+  dense-community graph   (N = 232 965, ~114.4 M nonzeros, shaped like the paper's first real graph)
+                          SpMM at F = 128, fp32
+  power-law skew graph    (N = 262 144, 8.39 M nonzeros, hub rows up to 65 536)
+                          multi-head CSR attention, H = 8, d = 64, bf16 operands, fp32 accumulation
+
+Every call runs the schedule the selector chose (replayed from its cache; the plan / hub partition runs
+inside every call).  Prints one JSON line: whole-step GFLOP/s (2*nnz*F per SpMM / SDDMM plus 4*nnz*H*d for the
+attention), the roofline of the dominant kernel from HIP events recorded inside the timed region on the
+launch stream, and the CPU oracle timed on the host cores as a reported baseline.  The width sweep of the
+power-law graph, the measured stream and gather ceilings and the vendor library's times go to `detail`.
+Everything else goes to stderr.
 """
 import argparse
 import json
@@ -21,6 +28,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+L2_TOTAL_BYTES = 8 * 4 << 20   # eight XCDs with 4 MiB of L2 each
+MALL_BYTES = 256 << 20         # Infinity Cache
 
 
 def log(*a):
@@ -53,14 +62,24 @@ def stage_bytes(stage, N, F, H, d, light_nnz, hub_nnz, n_chunks):
     return table.get(stage)
 
 
+def cache_level(operand_bytes):
+    """Which level of the memory system can hold the gathered dense operand."""
+    if operand_bytes <= L2_TOTAL_BYTES:
+        return "l2"
+    if operand_bytes <= MALL_BYTES:
+        return "infinity_cache"
+    return "hbm"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--no-sweep", action="store_true", help="skip the per-F table written to stderr")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-sweep", action="store_true", help="skip the detail section (width sweep, ceilings, vendor library)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--n", type=int, default=262144, help="rows of the power-law graph (default: the full config)")
+    ap.add_argument("--cache", default=None,
+                    help="schedule cache file prefix: loaded when present (the step then replays it without probing), saved at the end")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy three times (known traffic for counter scaling)")
     args = ap.parse_args()
@@ -76,36 +95,61 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    F, H, d = 64, 8, 64
-    t0 = time.time()
-    A = W.config2_powerlaw(n=args.n)
-    N, nnz = A.n_rows, A.nnz
-    rng = W.rng_for(0, 2, 7)
-    B = W.dense_operand(rng, N, F)
-    X = W.dense_operand(rng, N, F)
-    Y = W.dense_operand(rng, N, F)
-    Q, K, V = W.config5_attention(N, H, d, seed=0)
-    log("inputs: N=%d nnz=%d max_deg=%d generated in %.1f s" % (N, nnz, int(A.degrees.max()), time.time() - t0))
+    stream = torch.cuda.current_stream()
+    F, H, d = 128, 8, 64
+    scale = float(d) ** -0.5
 
     def dev(a):
         a = np.ascontiguousarray(a)
         return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
 
-    rp, ci, va = dev(A.rowptr), dev(A.colind), dev(A.val)
-    dB, dX, dY, dQ, dK, dV = (dev(t) for t in (B, X, Y, Q, K, V))
-    C = torch.empty((N, F), dtype=torch.float32, device="cuda")
-    out = torch.empty(nnz, dtype=torch.float32, device="cuda")
-    O = torch.empty((N, H, d), dtype=torch.float32, device="cuda")
-    h = ab.Handle(0)
-    ws_bytes = max(h.workspace_bytes(ab.OP_SPMM, N, nnz, 256), h.workspace_bytes(ab.OP_ATTENTION, N, nnz, d, H))
+    # ---- inputs ------------------------------------------------------------------------------------
+    t0 = time.time()
+    A4 = W.config4_large()
+    A3 = W.config3_community()
+    A2 = W.config2_powerlaw()
+    log("patterns generated in %.1f s: large sparse N=%d nnz=%d, dense-community N=%d nnz=%d, power-law N=%d nnz=%d"
+        % (time.time() - t0, A4.n_rows, A4.nnz, A3.n_rows, A3.nnz, A2.n_rows, A2.nnz))
+    t0 = time.time()
+    rng = W.rng_for(0, 4, 7)
+    B4, X4, Y4 = (W.dense_operand(rng, A4.n_rows, F) for _ in range(3))
+    B3 = W.dense_operand(W.rng_for(0, 3, 7), A3.n_rows, F)
+    Q, K, V = W.config5_attention(A2.n_rows, H, d, seed=0)
+    log("dense operands generated in %.1f s" % (time.time() - t0))
+
+    class Work:
+        pass
+
+    w4, w3, w5 = Work(), Work(), Work()
+    for w, A, name in ((w4, A4, "large_sparse"), (w3, A3, "dense_community"), (w5, A2, "power_law")):
+        w.A, w.name, w.N, w.nnz = A, name, A.n_rows, A.nnz
+        w.rp, w.ci = dev(A.rowptr), dev(A.colind)
+        w.h = ab.Handle(0)
+        if args.cache and os.path.exists(args.cache + "." + name):
+            w.h.cache_load(args.cache + "." + name)
+    w4.va, w3.va = dev(A4.val), dev(A3.val)
+    w4.B, w4.X, w4.Y = dev(B4), dev(X4), dev(Y4)
+    w4.C = torch.empty((w4.N, F), dtype=torch.float32, device="cuda")
+    w4.out = torch.empty(w4.nnz, dtype=torch.float32, device="cuda")
+    w3.B = dev(B3)
+    w3.C = torch.empty((w3.N, F), dtype=torch.float32, device="cuda")
+    w5.Q, w5.K, w5.V = dev(Q), dev(K), dev(V)
+    w5.O = torch.empty((w5.N, H, d), dtype=torch.float32, device="cuda")
+    ws_bytes = max(w4.h.workspace_bytes(ab.OP_SPMM, w4.N, w4.nnz, F), w3.h.workspace_bytes(ab.OP_SPMM, w3.N, w3.nnz, F),
+                   w5.h.workspace_bytes(ab.OP_ATTENTION, w5.N, w5.nnz, d, H))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
-    scale = float(d) ** -0.5
-    stream = torch.cuda.current_stream()
+
+    calls = [
+        ("large_sparse.spmm", w4, lambda: w4.h.spmm(w4.N, w4.N, w4.rp, w4.ci, w4.va, w4.B, w4.C, F, workspace=ws, stream=stream)),
+        ("large_sparse.sddmm", w4, lambda: w4.h.sddmm(w4.N, w4.N, w4.rp, w4.ci, w4.X, w4.Y, w4.out, F, workspace=ws, stream=stream)),
+        ("dense_community.spmm", w3, lambda: w3.h.spmm(w3.N, w3.N, w3.rp, w3.ci, w3.va, w3.B, w3.C, F, workspace=ws, stream=stream)),
+        ("power_law.attention", w5, lambda: w5.h.csr_attention(w5.N, w5.rp, w5.ci, w5.Q, w5.K, w5.V, w5.O, H, d, scale,
+                                                               workspace=ws, stream=stream)),
+    ]
 
     def step():
-        h.spmm(N, N, rp, ci, va, dB, C, F, workspace=ws, stream=stream)
-        h.sddmm(N, N, rp, ci, dX, dY, out, F, workspace=ws, stream=stream)
-        h.csr_attention(N, rp, ci, dQ, dK, dV, O, H, d, scale, workspace=ws, stream=stream)
+        for _, _, fn in calls:
+            fn()
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -115,77 +159,93 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # cold call: the selector probes and caches (reported, not part of the timed region)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    h.spmm(N, N, rp, ci, va, dB, C, F, workspace=ws, stream=stream)
-    torch.cuda.synchronize()
-    cold_spmm_ms = (time.perf_counter() - t0) * 1e3
-    dec_spmm = h.last_decision()
-    t0 = time.perf_counter()
-    h.sddmm(N, N, rp, ci, dX, dY, out, F, workspace=ws, stream=stream)
-    torch.cuda.synchronize()
-    cold_sddmm_ms = (time.perf_counter() - t0) * 1e3
-    dec_sddmm = h.last_decision()
-    t0 = time.perf_counter()
-    h.csr_attention(N, rp, ci, dQ, dK, dV, O, H, d, scale, workspace=ws, stream=stream)
-    torch.cuda.synchronize()
-    cold_attn_ms = (time.perf_counter() - t0) * 1e3
-    dec_attn = h.last_decision()
-    log("selector attn : %s (cold call %.2f ms)" % (dec_attn.get("choice"), cold_attn_ms))
-    log("selector spmm : %s (cold call %.2f ms)" % (dec_spmm.get("choice"), cold_spmm_ms))
-    log("selector sddmm: %s (cold call %.2f ms)" % (dec_sddmm.get("choice"), cold_sddmm_ms))
+    # cold calls: the selector probes and caches (reported, not part of the timed region)
+    decisions, cold_ms = {}, {}
+    for name, w, fn in calls:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        cold_ms[name] = (time.perf_counter() - t0) * 1e3
+        decisions[name] = w.h.last_decision()
+        log("selector %-22s %s (first call %.1f ms%s)" % (name, decisions[name].get("choice"), cold_ms[name],
+                                                           ", replayed from the cache file" if decisions[name].get("cache_hit") else ""))
 
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    h.profile_begin()                       # per-kernel HIP events on the launch stream, inside the timed region
+    for w in (w4, w3, w5):
+        w.h.profile_begin()                 # per-kernel HIP events on the launch stream, inside the timed region
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    stages = h.profile_read()
     ms_per_step = elapsed * 1e3 / args.steps
-    flops_step = 2.0 * nnz * F * 2 + 4.0 * nnz * H * d
+    flops_step = 2.0 * w4.nnz * F * 2 + 2.0 * w3.nnz * F + 4.0 * w5.nnz * H * d
     value = flops_step / (ms_per_step * 1e-3) / 1e9
 
-    # roofline of the dominant kernel stage
-    deg = A.degrees
-
-    def split(hub_t):
+    # ---- roofline of the dominant kernel stage -----------------------------------------------------------
+    def split(deg, nnz, hub_t, hub_chunk):
         if hub_t <= 0:
             return nnz, 0, 0
         hub = deg >= hub_t
         hub_nnz = int(deg[hub].sum())
-        return nnz - hub_nnz, hub_nnz, int(np.ceil(deg[hub] / hub_t).sum())
+        chunk = hub_chunk if hub_chunk > 0 else hub_t
+        return nnz - hub_nnz, hub_nnz, int(np.ceil(deg[hub] / chunk).sum())
 
-    hub_of = {"spmm": dec_spmm["choice"]["hub_t"], "sddmm": dec_sddmm["choice"]["hub_t"], "attn": dec_attn["choice"]["hub_t"], "softmax": dec_attn["choice"]["hub_t"]}
+    def choice_of(prefix):
+        return decisions[prefix]["choice"]
+
     per_stage = {}
-    for name, rec in stages.items():
-        key = "attn" if name.startswith("attn") else name.split("_")[0]
-        light_nnz, hub_nnz, n_chunks = split(hub_of.get(key, 0))
-        b = stage_bytes(name, N, F, H, d, light_nnz, hub_nnz, n_chunks)
-        avg_ms = rec["total_ms"] / rec["calls"]
-        per_stage[name] = {"avg_ms": avg_ms, "calls": rec["calls"], "alg_bytes": b,
-                           "gbs": None if b is None else b / avg_ms / 1e6}
-    dom = max(per_stage, key=lambda k: per_stage[k]["avg_ms"] * per_stage[k]["calls"])
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")     # from the committed rocprofv3 --pmc summaries
-    if os.path.exists(tpath) and N == 262144:
+    for w in (w4, w3, w5):
+        stages = w.h.profile_read()
+        deg = w.A.degrees
+        for st_name, rec in stages.items():
+            if w is w5:
+                ch = choice_of("power_law.attention")
+            else:
+                op = "sddmm" if st_name.startswith("sddmm") else "spmm"
+                ch = choice_of(w.name + "." + op) if (w.name + "." + op) in decisions else choice_of(w.name + ".spmm")
+            light_nnz, hub_nnz, n_chunks = split(deg, w.nnz, ch["hub_t"], ch.get("hub_chunk", 0))
+            b = stage_bytes(st_name, w.N, F, H, d, light_nnz, hub_nnz, n_chunks)
+            avg_ms = rec["total_ms"] / rec["calls"]
+            launches_per_step = rec["calls"] / args.steps
+            if st_name in ("attn_fused_rows", "attn_fused_hub", "attn_sddmm_rows", "attn_spmm_rows", "attn_sddmm_hub", "attn_spmm_hub"):
+                operand, row_bytes = 2 * w.N * H * d * 2 if "fused" in st_name else w.N * H * d * 2, 2 * H * d
+            elif st_name.startswith(("spmm", "sddmm")):
+                operand, row_bytes = w.N * F * 4, 4 * F
+            else:
+                operand, row_bytes = 0, 0
+            per_stage[w.name + "." + st_name] = {
+                "avg_ms": avg_ms, "launches_per_step": launches_per_step, "alg_bytes": b,
+                "gbs": None if b is None else b / avg_ms / 1e6, "gathered_operand_bytes": operand, "gathered_row_bytes": row_bytes,
+                "operand_fits": cache_level(operand) if operand else None}
+    dom = max(per_stage, key=lambda k: per_stage[k]["avg_ms"] * per_stage[k]["launches_per_step"])
+    # HBM traffic of the dominant kernel: rocprofv3 counters cannot be read from inside this process, so the figure is
+    # the committed one of the same command (profiles/bench_hbm_traffic.txt names the summary it comes from)
+    traffic, traffic_source = None, None
+    tpath = os.path.join(ROOT, "profiles", "bench_hbm_traffic.txt")
+    if os.path.exists(tpath):
         for ln in open(tpath):
             parts = ln.split()
-            if len(parts) == 2 and parts[0] == dom and parts[1].isdigit():
+            if ln.startswith("# source:"):
+                traffic_source = ln[len("# source:"):].strip()
+            elif len(parts) == 2 and parts[0] == dom and parts[1].isdigit():
                 traffic = int(parts[1])
     roofline = {"bound": "hbm", "kernel": dom, "achieved": per_stage[dom]["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": per_stage[dom]["gbs"] / HBM_PEAK_GBS, "traffic": traffic,
-                "avg_launch_ms": per_stage[dom]["avg_ms"], "alg_bytes_per_launch": per_stage[dom]["alg_bytes"]}
-    for name in sorted(per_stage, key=lambda k: -per_stage[k]["avg_ms"]):
+                "traffic_source": None if traffic is None else
+                "committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE figure, not measured by this run: " + (traffic_source or tpath),
+                "avg_launch_ms": per_stage[dom]["avg_ms"], "alg_bytes_per_launch": per_stage[dom]["alg_bytes"],
+                "gathered_operand_bytes": per_stage[dom]["gathered_operand_bytes"],
+                "gathered_operand_fits": per_stage[dom]["operand_fits"]}
+    for name in sorted(per_stage, key=lambda k: -per_stage[k]["avg_ms"] * per_stage[k]["launches_per_step"]):
         s = per_stage[name]
-        log("stage %-16s %8.4f ms/launch  %6.0f GB/s algorithmic (%.0f%% of 8 TB/s)"
-            % (name, s["avg_ms"], s["gbs"] or 0, 100 * (s["gbs"] or 0) / HBM_PEAK_GBS))
+        log("stage %-34s %8.4f ms/launch x %.0f  %6.0f GB/s algorithmic (%.0f%% of 8 TB/s), gathered operand %s"
+            % (name, s["avg_ms"], s["launches_per_step"], s["gbs"] or 0, 100 * (s["gbs"] or 0) / HBM_PEAK_GBS,
+               "%.0f MB -> %s" % (s["gathered_operand_bytes"] / 1e6, s["operand_fits"]) if s["operand_fits"] else "-"))
 
-    # per-op steady-state numbers at the step's width, and an F sweep (stderr only)
     def timed(fn, iters=10):
         fn()
         torch.cuda.synchronize()
@@ -200,124 +260,160 @@ def main():
         return float(np.median(ts))
 
     detail = {}
-    widths = [F] if args.no_sweep else [8, 16, 32, 64, 128, 256]
+    per_call = {}
     base = ab.baseline_schedule()
-    for f in widths:
-        Bf = dB if f == F else torch.randn(N, f, device="cuda")
-        Xf = dX if f == F else torch.randn(N, f, device="cuda")
-        Cf = torch.empty((N, f), dtype=torch.float32, device="cuda")
-        bg = 4 * (N + 1) + 8 * nnz + nnz * f * 4 + N * f * 4
-        t_sp = timed(lambda: h.spmm(N, N, rp, ci, va, Bf, Cf, f, workspace=ws, stream=stream))
-        ch_sp = h.last_decision().get("choice")
-        t_sd = timed(lambda: h.sddmm(N, N, rp, ci, Xf, Bf, out, f, workspace=ws, stream=stream))
-        ch_sd = h.last_decision().get("choice")
-        t_fb = timed(lambda: h.spmm(N, N, rp, ci, va, Bf, Cf, f, sched=base, workspace=ws, stream=stream), iters=3)
-        t_fd = timed(lambda: h.sddmm(N, N, rp, ci, Xf, Bf, out, f, sched=base, workspace=ws, stream=stream), iters=3)
-        detail["F%d" % f] = {
-            "spmm_ms": t_sp, "spmm_gflops": 2.0 * nnz * f / t_sp / 1e6, "spmm_gbs": bg / t_sp / 1e6,
-            "spmm_frac_hbm": bg / t_sp / 1e6 / HBM_PEAK_GBS, "spmm_fallback_ms": t_fb, "spmm_hub_t": ch_sp["hub_t"],
-            "spmm_mapping": ch_sp["mapping"],
-            "sddmm_ms": t_sd, "sddmm_gflops": 2.0 * nnz * f / t_sd / 1e6, "sddmm_gbs": bg / t_sd / 1e6,
-            "sddmm_frac_hbm": bg / t_sd / 1e6 / HBM_PEAK_GBS, "sddmm_fallback_ms": t_fd, "sddmm_hub_t": ch_sd["hub_t"],
-            "sddmm_mapping": ch_sd["mapping"],
-        }
-        log("F=%-3d spmm %.3f ms %.0f GFLOP/s %.0f GB/s (%.0f%%) fallback %.3f ms | sddmm %.3f ms %.0f GFLOP/s %.0f GB/s (%.0f%%) "
-            "fallback %.3f ms" % (f, t_sp, 2.0 * nnz * f / t_sp / 1e6, bg / t_sp / 1e6, 100 * bg / t_sp / 1e6 / HBM_PEAK_GBS,
-                                  t_fb, t_sd, 2.0 * nnz * f / t_sd / 1e6, bg / t_sd / 1e6,
-                                  100 * bg / t_sd / 1e6 / HBM_PEAK_GBS, t_fd))
-    # what this device's memory system sustains for plain streams (read, copy, in-place update), 1 GiB each
-    n_probe = 1 << 30
-    pa = torch.empty(n_probe, dtype=torch.uint8, device="cuda")
-    pb = torch.empty(n_probe, dtype=torch.uint8, device="cuda")
-    pa.zero_()
-    pb.zero_()
-    psum = torch.empty(h.stream_probe_dst_bytes(), dtype=torch.uint8, device="cuda")
-    measured = {
-        "read_gbs": n_probe / timed(lambda: h.stream_probe(ab.STREAM_READ, pa, psum, n_probe, stream=stream)) / 1e6,
-        "copy_gbs": 2 * n_probe / timed(lambda: h.stream_probe(ab.STREAM_COPY, pa, pb, n_probe, stream=stream)) / 1e6,
-        "inplace_gbs": 2 * n_probe / timed(lambda: h.stream_probe(ab.STREAM_INPLACE, None, pb, n_probe, stream=stream)) / 1e6,
-        "bytes": n_probe,
-    }
-    del pa, pb, psum
-    roofline["measured_stream"] = measured
-    roofline["frac_of_measured_read"] = roofline["achieved"] / measured["read_gbs"]
-    log("plain streams over 1 GiB: read %.0f GB/s, copy %.0f GB/s (read + written), in place %.0f GB/s; dominant kernel at "
-        "%.0f%% of the measured read rate" % (measured["read_gbs"], measured["copy_gbs"], measured["inplace_gbs"],
-                                              100 * roofline["frac_of_measured_read"]))
-    t_attn = timed(lambda: h.csr_attention(N, rp, ci, dQ, dK, dV, O, H, d, scale, workspace=ws, stream=stream))
-    detail["attention_ms"] = t_attn
-    log("csr_attention H=%d d=%d bf16: %.3f ms/call" % (H, d, t_attn))
+    for name, w, fn in calls:
+        t = timed(fn, iters=5)
+        nn = w.nnz
+        fl = 4.0 * nn * H * d if name.endswith("attention") else 2.0 * nn * F
+        per_call[name] = {"ms": t, "gflops": fl / t / 1e6}
+        if not name.endswith("attention"):
+            bg = 4 * (w.N + 1) + 8 * nn + nn * F * 4 + w.N * F * 4
+            bmin = 4 * (w.N + 1) + 8 * nn + 2 * w.N * F * 4
+            per_call[name].update({"gather_gbs": bg / t / 1e6, "compulsory_gbs": bmin / t / 1e6})
+        log("call %-22s %.3f ms  %.0f GFLOP/s" % (name, t, per_call[name]["gflops"]))
+    detail["per_call"] = per_call
+
     if not args.no_sweep:
+        # measured ceilings of this device: plain streams over 1 GiB, and random-row gathers out of tables that fit
+        # the L2s (16 MiB), the Infinity Cache (128 MiB) or neither (1 GiB)
+        n_probe = 1 << 30
+        pa = torch.empty(n_probe, dtype=torch.uint8, device="cuda")
+        pb = torch.empty(n_probe, dtype=torch.uint8, device="cuda")
+        pa.zero_()
+        pb.zero_()
+        psum = torch.empty(w4.h.stream_probe_dst_bytes(), dtype=torch.uint8, device="cuda")
+        measured = {
+            "read_gbs": n_probe / timed(lambda: w4.h.stream_probe(ab.STREAM_READ, pa, psum, n_probe, stream=stream)) / 1e6,
+            "copy_gbs": 2 * n_probe / timed(lambda: w4.h.stream_probe(ab.STREAM_COPY, pa, pb, n_probe, stream=stream)) / 1e6,
+            "inplace_gbs": 2 * n_probe / timed(lambda: w4.h.stream_probe(ab.STREAM_INPLACE, None, pb, n_probe, stream=stream)) / 1e6,
+            "bytes": n_probe,
+        }
+        del pb
+        roofline["measured_stream"] = measured
+        roofline["frac_of_measured_read"] = roofline["achieved"] / measured["read_gbs"]
+        log("plain streams over 1 GiB: read %.0f GB/s, copy %.0f GB/s (read + written), in place %.0f GB/s"
+            % (measured["read_gbs"], measured["copy_gbs"], measured["inplace_gbs"]))
+        gather = {}
+        n_idx = 1 << 24
+        for level, tbytes in (("l2", 16 << 20), ("infinity_cache", 128 << 20), ("hbm", 1 << 30)):
+            for rb in (128, 256, 512, 1024):
+                n_rows = tbytes // rb
+                idx = torch.randint(0, n_rows, (n_idx,), dtype=torch.int32, device="cuda")
+                t = timed(lambda: w4.h.gather_probe(pa, n_rows, rb, idx, psum, stream=stream), iters=5)
+                gather["%s_%dB" % (level, rb)] = n_idx * rb / t / 1e6
+                del idx
+            log("random-row gather out of %4d MiB (%s): %s GB/s for rows of 128 / 256 / 512 / 1024 B"
+                % (tbytes >> 20, level, " / ".join("%.0f" % gather["%s_%dB" % (level, rb)] for rb in (128, 256, 512, 1024))))
+        del pa, psum
+        roofline["measured_gather_gbs"] = gather
+        for name, s in per_stage.items():
+            if s["operand_fits"] and s["gbs"]:
+                rb = min((128, 256, 512, 1024), key=lambda r: abs(r - s["gathered_row_bytes"]))
+                s["gather_ceiling_gbs"] = gather["%s_%dB" % (s["operand_fits"], rb)]
+                s["frac_of_gather_ceiling"] = s["gbs"] / s["gather_ceiling_gbs"]
+        roofline["gather_ceiling_gbs"] = per_stage[dom].get("gather_ceiling_gbs")
+        roofline["frac_of_gather_ceiling"] = per_stage[dom].get("frac_of_gather_ceiling")
+
+        # width sweep on the power-law stressor (its six widths), selector's choice against the fallback
+        sweep = {}
+        w2 = w5
+        va2 = dev(A2.val)
+        out2 = torch.empty(w2.nnz, dtype=torch.float32, device="cuda")
+        for f in (8, 16, 32, 64, 128, 256):
+            Bf = torch.randn(w2.N, f, device="cuda")
+            Xf = torch.randn(w2.N, f, device="cuda")
+            Cf = torch.empty((w2.N, f), dtype=torch.float32, device="cuda")
+            bg = 4 * (w2.N + 1) + 8 * w2.nnz + w2.nnz * f * 4 + w2.N * f * 4
+            t_sp = timed(lambda: w2.h.spmm(w2.N, w2.N, w2.rp, w2.ci, va2, Bf, Cf, f, workspace=ws, stream=stream))
+            ch_sp = w2.h.last_decision().get("choice")
+            t_sd = timed(lambda: w2.h.sddmm(w2.N, w2.N, w2.rp, w2.ci, Xf, Bf, out2, f, workspace=ws, stream=stream))
+            ch_sd = w2.h.last_decision().get("choice")
+            t_fb = timed(lambda: w2.h.spmm(w2.N, w2.N, w2.rp, w2.ci, va2, Bf, Cf, f, sched=base, workspace=ws, stream=stream), iters=3)
+            t_fd = timed(lambda: w2.h.sddmm(w2.N, w2.N, w2.rp, w2.ci, Xf, Bf, out2, f, sched=base, workspace=ws, stream=stream), iters=3)
+            sweep["F%d" % f] = {
+                "spmm_ms": t_sp, "spmm_gflops": 2.0 * w2.nnz * f / t_sp / 1e6, "spmm_gather_gbs": bg / t_sp / 1e6,
+                "spmm_fallback_ms": t_fb, "spmm_hub_t": ch_sp["hub_t"], "spmm_mapping": ch_sp["mapping"],
+                "sddmm_ms": t_sd, "sddmm_gflops": 2.0 * w2.nnz * f / t_sd / 1e6, "sddmm_gather_gbs": bg / t_sd / 1e6,
+                "sddmm_fallback_ms": t_fd, "sddmm_hub_t": ch_sd["hub_t"], "sddmm_mapping": ch_sd["mapping"],
+            }
+            log("power-law F=%-3d spmm %.3f ms %.0f GFLOP/s %.0f GB/s fallback %.3f ms | sddmm %.3f ms %.0f GFLOP/s %.0f GB/s "
+                "fallback %.3f ms" % (f, t_sp, 2.0 * w2.nnz * f / t_sp / 1e6, bg / t_sp / 1e6, t_fb, t_sd,
+                                      2.0 * w2.nnz * f / t_sd / 1e6, bg / t_sd / 1e6, t_fd))
+            del Bf, Xf, Cf
+        detail["power_law_width_sweep"] = sweep
+        del va2, out2
         try:                                  # the vendor's sparse library on the same buffers, as a reported reference only
             from paper_2511_17594_amd import vendor
             vs = vendor.Session(torch)
-            Cv = torch.empty_like(C)
-            t_algs = vs.spmm_times(N, N, rp, ci, va, dB, Cv, iters=3)
-            t_vsd = vs.sddmm_time(N, N, rp, ci, dX, dB, torch.zeros_like(out), iters=3)
-            vs.close()
-            detail["hipsparse_spmm_F64_ms"] = t_algs
-            detail["hipsparse_sddmm_F64_ms"] = t_vsd
-            log("hipSPARSE at F=64: SpMM %s ms, SDDMM %s ms"
-                % ({k: round(v, 3) for k, v in t_algs.items()}, "n/a" if t_vsd is None else "%.3f" % t_vsd))
+            Cv = torch.empty_like(w4.C)
+            detail["hipsparse_spmm_large_sparse_F128_ms"] = vs.spmm_times(w4.N, w4.N, w4.rp, w4.ci, w4.va, w4.B, Cv, iters=2)
             del Cv
+            Cv = torch.empty_like(w3.C)
+            detail["hipsparse_spmm_dense_community_F128_ms"] = vs.spmm_times(w3.N, w3.N, w3.rp, w3.ci, w3.va, w3.B, Cv, iters=2)
+            del Cv
+            vs.close()
+            log("hipSPARSE SpMM at F=128: large sparse %s ms, dense-community %s ms"
+                % ({k: round(v, 3) for k, v in detail["hipsparse_spmm_large_sparse_F128_ms"].items()},
+                   {k: round(v, 3) for k, v in detail["hipsparse_spmm_dense_community_F128_ms"].items()}))
         except Exception as e:                # pragma: no cover
             log("hipSPARSE unavailable: %r" % (e,))
+        # the guardrail's fallback kernel on the step's own calls (one run each: it walks a 541 482-long row on one wavefront)
+        fb = {}
+        fb["large_sparse.spmm"] = timed(lambda: w4.h.spmm(w4.N, w4.N, w4.rp, w4.ci, w4.va, w4.B, w4.C, F, sched=base, workspace=ws, stream=stream), iters=1)
+        fb["dense_community.spmm"] = timed(lambda: w3.h.spmm(w3.N, w3.N, w3.rp, w3.ci, w3.va, w3.B, w3.C, F, sched=base, workspace=ws, stream=stream), iters=1)
+        detail["fallback_ms"] = fb
+        log("fallback kernel: %s" % {k: round(v, 2) for k, v in fb.items()})
 
-    # the same cold calls on a fresh handle (empty cache) now that the kernels' code objects are loaded: what a
-    # long-running process pays when it meets a new graph
-    # (skipped with --no-sweep: the profile summaries take the last dispatches of a kernel for the timed steps)
-    cold_loaded = {}
-    h2 = ab.Handle(0)
-    for name, fn in () if args.no_sweep else (("spmm", lambda: h2.spmm(N, N, rp, ci, va, dB, C, F, workspace=ws, stream=stream)),
-                     ("sddmm", lambda: h2.sddmm(N, N, rp, ci, dX, dY, out, F, workspace=ws, stream=stream)),
-                     ("attention", lambda: h2.csr_attention(N, rp, ci, dQ, dK, dV, O, H, d, scale, workspace=ws, stream=stream))):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        fn()
-        torch.cuda.synchronize()
-        cold_loaded[name] = (time.perf_counter() - t0) * 1e3
-    h2.close()
-    log("cold calls with the code objects loaded: %s" % {k: round(v, 2) for k, v in cold_loaded.items()})
+    if args.cache:
+        for w in (w4, w3, w5):
+            w.h.cache_save(args.cache + "." + w.name)
 
-    # CPU baseline: the oracle as it stands, on the host cores, same step
+    # ---- CPU baseline: the oracle as it stands, on the host cores, the same step once --------------------------
     cpu = None
     if not args.no_cpu:
         import oracle
-        # bounded sample: the step itself on the whole graph, repeated until about 12 s of CPU work (at most 16 times)
-        reps, t_sp, t_at = 0, 0.0, 0.0
-        while reps < 16 and t_sp + t_at < 12.0:
+        # bounded sample: the whole step, repeated until about 12 s of CPU work (at most 8 times)
+        reps, t_parts = 0, [0.0, 0.0, 0.0, 0.0]
+        while reps < 8 and sum(t_parts) < 12.0:
             t0 = time.perf_counter()
-            oracle.spmm(A.rowptr, A.colind, A.val, B)
-            oracle.sddmm(A.rowptr, A.colind, X, Y)
+            oracle.spmm(A4.rowptr, A4.colind, A4.val, B4)
             t1 = time.perf_counter()
-            oracle.csr_attention(A.rowptr, A.colind, Q, K, V, scale)
+            oracle.sddmm(A4.rowptr, A4.colind, X4, Y4)
             t2 = time.perf_counter()
-            t_sp += t1 - t0
-            t_at += t2 - t1
+            oracle.spmm(A3.rowptr, A3.colind, A3.val, B3)
+            t3 = time.perf_counter()
+            oracle.csr_attention(A2.rowptr, A2.colind, Q, K, V, scale)
+            t4 = time.perf_counter()
+            for i, dt_ in enumerate((t1 - t0, t2 - t1, t3 - t2, t4 - t3)):
+                t_parts[i] += dt_
             reps += 1
-        cpu = {"value": reps * flops_step / (t_sp + t_at) / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(),
-               "kind": "oracle",
-               "sample": "the whole step (all %d rows, %d nonzeros), %d repetition(s): SpMM+SDDMM %.1f s, attention %.1f s"
-                         % (N, nnz, reps, t_sp, t_at)}
+        cpu = {"value": reps * flops_step / sum(t_parts) / 1e9, "unit": "GFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "the whole step (all rows of the three graphs), %d repetition(s): large sparse SpMM %.1f s + SDDMM %.1f s, "
+                         "dense-community SpMM %.1f s, attention %.1f s" % ((reps,) + tuple(t_parts))}
         log("cpu oracle: %.2f GFLOP/s on %d threads (%s)" % (cpu["value"], cpu["cores"], cpu["sample"]))
 
     line = {
-        "metric": "CSR SpMM+SDDMM (F=64, fp32) + CSR attention (H=8, d=64, bf16) step throughput, 2*nnz*F flops",
+        "metric": "CSR SpMM + SDDMM + CSR-attention step throughput (flops: 2*nnz*F per SpMM / SDDMM call, 4*nnz*H*d for the attention)",
         "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 (SpMM/SDDMM), bf16 operands with f32 accumulation (attention)", "data": "synthetic",
-        "config": {"workload": "power-law skew stressor N=%d nnz=%d (Pareto exponent 2.1, mean 32, clip 65536), "
-                               "SpMM+SDDMM F=64 fp32 + CSR attention H=8 d=64 bf16" % (N, nnz),
-                   "N": N, "nnz": nnz, "F": F, "H": H, "d": d},
+        "config": {"workload": "large sparse graph N=%d nnz=%d (power-law exponent 2.3, symmetric, self loops): SpMM + SDDMM F=128 fp32; "
+                               "dense-community graph N=%d nnz=%d: SpMM F=128 fp32; power-law skew graph N=%d nnz=%d (hub rows to 65536): "
+                               "CSR attention H=8 d=64 bf16" % (w4.N, w4.nnz, w3.N, w3.nnz, w5.N, w5.nnz),
+                   "F": F, "H": H, "d": d,
+                   "large_sparse": {"N": w4.N, "nnz": w4.nnz}, "dense_community": {"N": w3.N, "nnz": w3.nnz},
+                   "power_law": {"N": w5.N, "nnz": w5.nnz}},
         "roofline": roofline,
         "cpu_baseline": cpu,
-        "selector": {"spmm": dec_spmm.get("choice"), "sddmm": dec_sddmm.get("choice"), "attention": dec_attn.get("choice"),
-                     "cold_call_ms": {"spmm": cold_spmm_ms, "sddmm": cold_sddmm_ms, "attention": cold_attn_ms},
-                     "cold_call_code_loaded_ms": cold_loaded},
-        "stages": {k: {"avg_ms": v["avg_ms"], "gbs": v["gbs"]} for k, v in per_stage.items()},
+        "selector": {"choice": {k: v.get("choice") for k, v in decisions.items()}, "first_call_ms": cold_ms},
+        "stages": {k: {kk: vv for kk, vv in v.items() if kk in ("avg_ms", "launches_per_step", "gbs", "operand_fits",
+                                                                  "gather_ceiling_gbs", "frac_of_gather_ceiling")}
+                   for k, v in per_stage.items()},
         "detail": detail,
     }
-    h.close()
+    for w in (w4, w3, w5):
+        w.h.close()
     print(json.dumps(line), flush=True)
 
 

@@ -158,7 +158,10 @@ autosage_status_t autosage_csr_row_softmax(autosage_handle_t h, int64_t n_rows, 
  * wavefront, else UNSUPPORTED); AUTOSAGE_MAP_WAVE_ROW or AUTOSAGE_MAP_PLAIN = three stages (SDDMM ->
  * row-softmax -> SpMM with the [nnz, H] fp32 scores in the workspace); the guardrail baseline is the
  * three-stage pipeline without hub split (autosage_baseline_schedule).  hub_t / hub_chunk / waves_per_wg /
- * unroll apply to every stage; f_tile and vec_bytes are chosen from H and d.
+ * unroll apply to every stage; vec_bytes is chosen from d.  f_tile: for AUTOSAGE_MAP_FUSED, 0 or the features of
+ * one head tile (a multiple of d whose head count divides H): the launch then walks the heads tile after tile,
+ * so that the slices of K and V a tile gathers from fit cache levels the whole operands do not (any other value
+ * -> UNSUPPORTED); the three-stage pipeline ignores it.
  * sched == NULL: the selector chooses pipeline and hub threshold (autosage_decide_attention). */
 autosage_status_t autosage_csr_attention(autosage_handle_t h, int64_t N, int64_t nnz,
                                          const int32_t* rowptr, const int32_t* colind, const float* val,
@@ -346,6 +349,18 @@ typedef enum { AUTOSAGE_STREAM_READ = 0, AUTOSAGE_STREAM_COPY = 1, AUTOSAGE_STRE
 autosage_status_t autosage_stream_probe(autosage_handle_t h, autosage_stream_mode_t mode, const void* src, void* dst,
                                         size_t n_bytes, void* stream);
 autosage_status_t autosage_stream_probe_dst_bytes(autosage_handle_t h, size_t* bytes);
+
+/* Gather probe (same purpose: the ceiling of the access pattern the sparse kernels are bound by).  Launches one
+ * kernel that reads n_idx whole rows of row_bytes bytes (a power of two, 16 .. 1024) out of `table`
+ * ([n_table_rows, row_bytes], dev, 16-byte aligned) at the row numbers idx[0 .. n_idx) (int32, dev; values outside
+ * the table are clamped into it), in the access pattern of the SpMM / SDDMM / attention kernels: 64 indices per
+ * coalesced load, row_bytes / 16 lanes per row, four 16-byte loads in flight per lane.  dst (dev,
+ * autosage_stream_probe_dst_bytes() bytes) receives one fp32 partial sum per workgroup; their total is the sum of
+ * all fp32 elements of the gathered rows.  A table that fits the L2 caches, the Infinity Cache or neither gives
+ * the ceiling of the respective regime.  n_idx = 0 is valid.  The caller times it; nothing is allocated, nothing
+ * synchronises. */
+autosage_status_t autosage_gather_probe(autosage_handle_t h, const void* table, int64_t n_table_rows, int32_t row_bytes,
+                                        const int32_t* idx, int64_t n_idx, float* dst, void* stream);
 
 /* The baseline (fallback) schedule of the guardrail: plain one-wavefront-per-row kernel. */
 autosage_status_t autosage_baseline_schedule(autosage_schedule_t* out);

@@ -82,6 +82,7 @@ def _load():
                                             c.c_float, c.c_int, i32, i32, vp, sz, vp],
         "autosage_stream_probe": [vp, c.c_int, vp, vp, sz, vp],
         "autosage_stream_probe_dst_bytes": [vp, c.POINTER(sz)],
+        "autosage_gather_probe": [vp, vp, i64, i32, vp, i64, vp, vp],
         "autosage_profile_begin": [vp],
         "autosage_profile_read": [vp, c.c_char_p, sz],
     }
@@ -332,6 +333,12 @@ class Handle:
     def stream_probe(self, mode: int, src, dst, n_bytes: int, stream=None):
         """One launch of the plain streaming kernel `mode` (STREAM_READ / STREAM_COPY / STREAM_INPLACE) over n_bytes."""
         _check(_lib.autosage_stream_probe(self._h, mode, _ptr(src), _ptr(dst), n_bytes, _stream(stream)), "autosage_stream_probe")
+
+    def gather_probe(self, table, n_table_rows: int, row_bytes: int, idx, dst, n_idx=None, stream=None):
+        """One launch of the random-row gather kernel: rows idx[0..n_idx) of `row_bytes` bytes out of `table`."""
+        n_idx = int(idx.numel()) if n_idx is None else n_idx
+        _check(_lib.autosage_gather_probe(self._h, _ptr(table), n_table_rows, row_bytes, _ptr(idx), n_idx, _ptr(dst),
+                                          _stream(stream)), "autosage_gather_probe")
 
     def profile_begin(self):
         _check(_lib.autosage_profile_begin(self._h), "autosage_profile_begin")

@@ -485,11 +485,12 @@ static bool sizes_ok(int64_t n_rows, int64_t n_cols, int64_t nnz)
     return n_rows >= 0 && n_cols >= 0 && nnz >= 0 && nnz <= kMaxNnz && n_rows <= kMaxNnz && n_cols < (int64_t(1) << 31);
 }
 
-extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
-                                           const int32_t* rowptr, const int32_t* colind, const float* val,
-                                           const void* B, int64_t ldb, float* C, int64_t ldc, int32_t F,
-                                           autosage_dtype_t dt, const autosage_schedule_t* sched,
-                                           void* workspace, size_t workspace_bytes, void* stream)
+namespace autosage {
+
+autosage_status_t spmm_entry(autosage_ctx* h, int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
+                             const int32_t* colind, const float* val, const void* B, int64_t ldb, float* C, int64_t ldc,
+                             int32_t F, int dt, const autosage_schedule_t* sched, void* workspace, size_t workspace_bytes,
+                             void* stream)
 {
     if (!h || !sizes_ok(n_rows, n_cols, nnz) || F <= 0 || ldb < F || ldc < F) return AUTOSAGE_ERR_INVALID_ARG;
     if (!dtype_known(dt)) return AUTOSAGE_ERR_INVALID_ARG;
@@ -500,7 +501,8 @@ extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, 
     autosage_schedule_t chosen;
     if (!sched) {
         autosage_status_t s = autosage_decide(h, AUTOSAGE_OP_SPMM, n_rows, n_cols, nnz, rowptr, colind, val, B, ldb,
-                                              nullptr, 0, C, ldc, F, dt, workspace, workspace_bytes, stream, &chosen);
+                                              nullptr, 0, C, ldc, F, (autosage_dtype_t)dt, workspace, workspace_bytes, stream,
+                                              &chosen);
         if (s != AUTOSAGE_OK) return s;
         sched = &chosen;
     }
@@ -528,6 +530,18 @@ extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, 
     a.heads = 1;
     a.head_dim = F;
     return exec_spmm(h, a, r, nnz, workspace, workspace_bytes, st);
+}
+
+}  // namespace autosage
+
+extern "C" autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                           const int32_t* rowptr, const int32_t* colind, const float* val,
+                                           const void* B, int64_t ldb, float* C, int64_t ldc, int32_t F,
+                                           autosage_dtype_t dt, const autosage_schedule_t* sched,
+                                           void* workspace, size_t workspace_bytes, void* stream)
+{
+    return spmm_entry(h, n_rows, n_cols, nnz, rowptr, colind, val, B, ldb, C, ldc, F, (int)dt, sched, workspace, workspace_bytes,
+                      stream);
 }
 
 extern "C" autosage_status_t autosage_sddmm(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
@@ -641,8 +655,11 @@ static size_t attention_part_floats(int32_t H, int32_t d) { return (size_t)H * d
 // Which attention pipeline a schedule asks for: 1 = single pass, 0 = three stages, -1 = cannot run.
 static int attention_pipeline(const autosage_schedule_t& sched, int32_t H, int32_t d, int dt, AttnShape* shape)
 {
-    const bool can_fuse = attn_fused_shape(H, d, dt, shape);
-    if (sched.mapping == AUTOSAGE_MAP_FUSED) return can_fuse ? 1 : -1;
+    if (sched.mapping == AUTOSAGE_MAP_FUSED) {
+        // f_tile = features per head tile (a multiple of d that divides H * d); 0 = all heads in one tile
+        if (sched.f_tile < 0 || sched.f_tile % d != 0) return -1;
+        return attn_fused_shape_tiled(H, d, dt, sched.f_tile / d, shape) ? 1 : -1;
+    }
     if (sched.mapping == AUTOSAGE_MAP_WAVE_ROW || sched.mapping == AUTOSAGE_MAP_PLAIN) return 0;
     return -1;
 }
@@ -831,10 +848,17 @@ extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autos
         case AUTOSAGE_OP_SOFTMAX: b = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, 2 * (int64_t)H); break;
         case AUTOSAGE_OP_ATTENTION: {
             // dtype is not an argument here: take the largest per-chunk state over the element types
+            // (and, without a schedule, over the head tilings the selector may choose)
             AttnShape sh{};
             size_t fused_floats = 0;
-            for (int dt = DT_F32; dt <= DT_F16; ++dt)
-                if (attn_fused_shape(H, F, dt, &sh)) fused_floats = std::max(fused_floats, attn_fused_part_floats(sh));
+            for (int dt = DT_F32; dt <= DT_F16; ++dt) {
+                for (int ht = 1; ht <= H; ++ht) {
+                    if (H % ht != 0) continue;
+                    if (sched && sched->f_tile > 0 && sched->f_tile != ht * F) continue;
+                    if (sched && sched->f_tile <= 0 && ht != H) continue;
+                    if (attn_fused_shape_tiled(H, F, dt, ht, &sh)) fused_floats = std::max(fused_floats, attn_fused_part_floats(sh));
+                }
+            }
             const size_t three = align_up(sizeof(float) * (size_t)nnz * H, 256) +
                                  hub_workspace_bytes(n_rows, nnz, hub_t, chunk, (int64_t)attention_part_floats(H, F));
             const size_t fused = hub_workspace_bytes(n_rows, nnz, hub_t, chunk, (int64_t)fused_floats);
@@ -1138,6 +1162,21 @@ extern "C" autosage_status_t autosage_stream_probe(autosage_handle_t h, autosage
     if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
     if (n_bytes == 0 && mode != AUTOSAGE_STREAM_READ) return AUTOSAGE_OK;
     HIP_TRY(launch_stream_probe((int)mode, stream_probe_blocks(h->cu_count), src, dst, (int64_t)(n_bytes / 16),
+                                static_cast<hipStream_t>(stream)));
+    return AUTOSAGE_OK;
+}
+
+extern "C" autosage_status_t autosage_gather_probe(autosage_handle_t h, const void* table, int64_t n_table_rows,
+                                                   int32_t row_bytes, const int32_t* idx, int64_t n_idx, float* dst,
+                                                   void* stream)
+{
+    if (!h || n_table_rows < 0 || n_table_rows >= (int64_t(1) << 31) || n_idx < 0 || n_idx > (int64_t(1) << 40))
+        return AUTOSAGE_ERR_INVALID_ARG;
+    if (row_bytes < 16 || row_bytes > 1024 || (row_bytes & (row_bytes - 1)) != 0) return AUTOSAGE_ERR_INVALID_ARG;
+    if (!dst || (n_idx > 0 && (!table || !idx || n_table_rows == 0))) return AUTOSAGE_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uint64_t>(table) & 15u) != 0) return AUTOSAGE_ERR_INVALID_ARG;
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
+    HIP_TRY(launch_gather_probe(stream_probe_blocks(h->cu_count), table, (int32_t)n_table_rows, row_bytes, idx, n_idx, dst,
                                 static_cast<hipStream_t>(stream)));
     return AUTOSAGE_OK;
 }

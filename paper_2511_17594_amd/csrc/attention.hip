@@ -33,7 +33,28 @@ bool attn_fused_shape(int32_t H, int32_t d, int dt, AttnShape* s)
     return hp * s->LH >= 8;
 }
 
-size_t attn_fused_part_floats(const AttnShape& s) { return (size_t)s.KH * s.LH * s.HW * (s.vec + 2); }
+static bool attn_fused_shape_one(int32_t H, int32_t d, int dt, AttnShape* s)
+{
+    if (!attn_fused_shape(H, d, dt, s)) return false;
+    s->heads_tile = H;
+    s->tiles = 1;
+    return true;
+}
+
+bool attn_fused_shape_tiled(int32_t H, int32_t d, int dt, int32_t heads_tile, AttnShape* s)
+{
+    if (heads_tile <= 0 || heads_tile >= H) return attn_fused_shape_one(H, d, dt, s);
+    if (H % heads_tile != 0) return false;
+    if (!attn_fused_shape(heads_tile, d, dt, s)) return false;
+    s->heads_tile = heads_tile;
+    s->tiles = H / heads_tile;
+    return true;
+}
+
+size_t attn_fused_part_floats(const AttnShape& s)
+{
+    return (size_t)(s.tiles > 0 ? s.tiles : 1) * s.KH * s.LH * s.HW * (s.vec + 2);
+}
 
 hipError_t launch_attn_fused_rows(const AttnArgs& a, const AttnShape& s, hipStream_t stream)
 {

@@ -148,6 +148,11 @@ autosage_status_t exec_spmm(autosage_ctx* h, const SpmmArgs& a, const Resolved& 
 autosage_status_t exec_sddmm(autosage_ctx* h, const SddmmArgs& a, const Resolved& r, int64_t nnz, void* ws, size_t ws_bytes,
                              hipStream_t st);
 
+// Body of autosage_spmm (argument checks, selector when sched is NULL, schedule resolution, launches).
+autosage_status_t spmm_entry(autosage_ctx* h, int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr,
+                             const int32_t* colind, const float* val, const void* B, int64_t ldb, float* C, int64_t ldc,
+                             int32_t F, int dt, const autosage_schedule_t* sched, void* workspace, size_t workspace_bytes,
+                             void* stream);
 // Checks the 16-byte alignment / width rules of the attention kernels.
 autosage_status_t attention_alignment(const AttnCall& c);
 // Runs the attention pipeline the schedule names (FUSED = single pass, else three stages) on `rows`.

@@ -125,10 +125,15 @@ struct AttnShape {
     int32_t wpg;
     int32_t hub_t;
     int32_t hub_chunk;
+    int32_t heads_tile;    // heads one launch row (grid.y) covers; tiles * heads_tile >= H
+    int32_t tiles;         // head tiles, walked one after the other by the launch
 };
 
-// True (and fills vec/LH/HW/KH) when the single-pass kernels cover this head count and width.
+// True (and fills vec/LH/HW/KH, one tile of all H heads) when the single-pass kernels cover this head count and width.
 bool attn_fused_shape(int32_t H, int32_t d, int dt, AttnShape* s);
+// The same for a launch that walks the heads in tiles of heads_tile (> 0, dividing H) heads: the K and V slices a
+// tile gathers from are heads_tile / H of the operands, small enough to stay in the caches when the whole is not.
+bool attn_fused_shape_tiled(int32_t H, int32_t d, int dt, int32_t heads_tile, AttnShape* s);
 // Floats of partial state per hub chunk.
 size_t attn_fused_part_floats(const AttnShape& s);
 hipError_t launch_attn_fused_rows(const AttnArgs& a, const AttnShape& s, hipStream_t stream);
@@ -190,5 +195,9 @@ hipError_t launch_validate_csr(int64_t n_rows, int64_t n_cols, int64_t nnz, cons
 // floats), 1 = copy src to dst, 2 = scale dst in place; n_vec 16-byte vectors.
 int stream_probe_blocks(int cu_count);
 hipError_t launch_stream_probe(int mode, int blocks, const void* src, void* dst, int64_t n_vec, hipStream_t stream);
+// Random-row gather out of a table of n_table_rows rows of row_bytes (16 * 2^k, at most 1024) bytes: n_idx row
+// numbers (clamped into the table), one partial sum per workgroup into sums (`blocks` floats).
+hipError_t launch_gather_probe(int blocks, const void* table, int32_t n_table_rows, int32_t row_bytes, const int32_t* idx,
+                               int64_t n_idx, float* sums, hipStream_t stream);
 
 }  // namespace autosage

@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 from paper_2511_17594_amd import workloads as W
-from util import dev, rel_l1_rows, rel_l1_segments
+from util import BACKWARD_FLOOR, dev, rel_l1_rows, rel_l1_segments, stats_line
 
 pytestmark = pytest.mark.gpu
 
@@ -52,8 +52,15 @@ def check_spmm(torch, ab, handle, A, d_csr, F, rows, seed, sched=None):
     As = W.row_slice(A, rows)
     ref = oracle.spmm(As.rowptr, As.colind, As.val, B)
     ref_abs = oracle.spmm(As.rowptr, As.colind, np.abs(As.val), np.abs(B))
-    err = rel_l1_rows(got, ref, ref_abs)
+    st = {}
+    err = rel_l1_rows(got, ref, ref_abs, terms=As.degrees, stats=st)
+    hub = As.degrees >= 1024
+    plain = rel_l1_rows(got, ref)
+    print(stats_line("spmm F=%d" % F, st) + "; plain max on the %d sampled rows of 1024 entries or more: %.2e"
+          % (int(hub.sum()), float(plain[hub].max()) if hub.any() else 0.0), flush=True)
     assert err.max() <= 1e-5, (F, float(err.max()), int(rows[err.argmax()]))
+    if F >= 8:
+        assert st["floored_rows"] == 0          # no sampled row of these inputs cancels: every one is held to the plain 1e-5
     return C
 
 
@@ -73,7 +80,12 @@ def check_sddmm(torch, ab, handle, A, d_csr, F, rows, seed, sched=None):
     Xs = np.ascontiguousarray(X[rows])
     ref = oracle.sddmm(As.rowptr, As.colind, Xs, Y)
     ref_abs = oracle.sddmm(As.rowptr, As.colind, np.abs(Xs), np.abs(Y))
-    err = rel_l1_segments(got, ref, As.rowptr, ref_abs)
+    st = {}
+    err = rel_l1_segments(got, ref, As.rowptr, ref_abs, terms=F, stats=st)
+    hub = As.degrees >= 1024
+    plain = rel_l1_segments(got, ref, As.rowptr)
+    print(stats_line("sddmm F=%d" % F, st) + "; plain max on the %d sampled rows of 1024 entries or more: %.2e"
+          % (int(hub.sum()), float(plain[hub].max()) if hub.any() else 0.0), flush=True)
     assert err.max() <= 1e-5, (F, float(err.max()), int(rows[err.argmax()]))
 
 
@@ -89,10 +101,10 @@ def test_config1_tiny_full_compare(torch, ab, handle):
     torch.cuda.synchronize()
     ref = oracle.spmm(A.rowptr, A.colind, A.val, B)
     ref_abs = oracle.spmm(A.rowptr, A.colind, np.abs(A.val), np.abs(B))
-    assert rel_l1_rows(C.cpu().numpy(), ref, ref_abs).max() <= 1e-5
+    assert rel_l1_rows(C.cpu().numpy(), ref, ref_abs, terms=A.degrees).max() <= 1e-5
     ref = oracle.sddmm(A.rowptr, A.colind, X, Y)
     ref_abs = oracle.sddmm(A.rowptr, A.colind, np.abs(X), np.abs(Y))
-    assert rel_l1_segments(out.cpu().numpy(), ref, A.rowptr, ref_abs).max() <= 1e-5
+    assert rel_l1_segments(out.cpu().numpy(), ref, A.rowptr, ref_abs, terms=32).max() <= 1e-5
 
 
 def check_row_softmax(torch, ab, handle, A, d_rowptr, H, hub_t, rows, seed):
@@ -127,7 +139,7 @@ def check_row_softmax(torch, ab, handle, A, d_rowptr, H, hub_t, rows, seed):
                                                                     / np.maximum(P_h.astype(np.float64), 1e-300) + np.abs(dP_h)))
     for h in range(H):
         assert rel_l1_segments(P_h[:, h], ref[:, h], As.rowptr).max() <= 1e-5, (H, hub_t, h)
-        assert rel_l1_segments(dS_h[:, h], ref_b[:, h], As.rowptr, mag_b[:, h]).max() <= 1e-5, (H, hub_t, h)
+        assert rel_l1_segments(dS_h[:, h], ref_b[:, h], As.rowptr, mag_b[:, h], floors=(BACKWARD_FLOOR, BACKWARD_FLOOR)).max() <= 1e-5, (H, hub_t, h)
 
 
 @pytest.fixture(scope="module")
@@ -137,7 +149,7 @@ def config2():
     return A
 
 
-@pytest.mark.parametrize("F", [8, 64, 256])
+@pytest.mark.parametrize("F", [8, 16, 32, 64, 128, 256])
 def test_config2_powerlaw_full_size(torch, ab, handle, config2, F):
     A = config2
     d_csr = (dev(A.rowptr, torch), dev(A.colind, torch), dev(A.val, torch))
@@ -188,37 +200,78 @@ def test_config5_attention_full_size(torch, ab, handle, config2):
             assert bool(torch.isfinite(O).all())
             got = O[torch.from_numpy(rows).cuda()].cpu().numpy()
             err = rel_l1_rows(got.reshape(-1, d), ref.reshape(-1, d))
+            print("attention qk_std=%s %s: per-(row, head) error max %.2e" % (qk_std, "selector" if sched is None else "three stages",
+                                                                           float(err.max())), flush=True)
             assert err.max() <= 2e-2, (qk_std, float(err.max()))
+            # the bf16 inputs are exact in both paths: what is left is fp32 rounding, far below the stated 2e-2
+            assert err.max() <= 1e-4, (qk_std, float(err.max()))
             # every output row is a convex combination of V rows: bounded by the extreme V value
             assert float(O.abs().max()) <= vmax * (1 + 1e-5)
             del O, ws
 
 
-def test_config3_community_full_size(torch, ab, handle):
+@pytest.fixture(scope="module")
+def config3(torch):
     A = W.config3_community()
     assert A.n_rows == 232965 and abs(A.nnz / 114.6e6 - 1) < 0.03
-    d_csr = (dev(A.rowptr, torch), dev(A.colind, torch), dev(A.val, torch))
+    return A, (dev(A.rowptr, torch), dev(A.colind, torch), dev(A.val, torch))
+
+
+@pytest.mark.parametrize("F", [32, 64, 128, 256, 602])
+def test_config3_community_full_size(torch, ab, handle, config3, F):
+    A, d_csr = config3
     rows = sample_rows(A, 300, 3)
-    for F in (128, 602):
-        check_spmm(torch, ab, handle, A, d_csr, F, rows, seed=F)
-    # val = 1/deg(i): A times the all-ones matrix is all ones (any size, no oracle needed)
+    check_spmm(torch, ab, handle, A, d_csr, F, rows, seed=F)
+
+
+def test_config3_row_normalised_ones(torch, ab, handle, config3):
+    """val = 1/deg(i): A times the all-ones matrix is all ones (every row, no oracle needed, nothing cancels)."""
+    A, d_csr = config3
     F = 32
     ones = torch.ones((A.n_cols, F), dtype=torch.float32, device="cuda")
     C = torch.empty((A.n_rows, F), dtype=torch.float32, device="cuda")
     ws = torch.empty(handle.workspace_bytes(ab.OP_SPMM, A.n_rows, A.nnz, F), dtype=torch.uint8, device="cuda")
     handle.spmm(A.n_rows, A.n_cols, *d_csr, ones, C, F, workspace=ws)
     torch.cuda.synchronize()
-    assert float((C - 1.0).abs().max()) <= 2e-5
+    assert float((C - 1.0).abs().max()) <= 1e-5
 
 
-def test_config4_large_sparse_full_size(torch, ab, handle):
+def test_config3_no_cancellation_plain_metric(torch, ab, handle, config3):
+    """val = 1/deg(i) > 0 and B >= 0: no term cancels, so the plain per-row 1e-5 is asserted on every sampled row
+    without any floor (ref_abs is not even passed)."""
+    A, d_csr = config3
+    F = 128
+    rows = sample_rows(A, 300, 33)
+    rng = np.random.default_rng(33)
+    B = np.abs(rng.standard_normal((A.n_cols, F), dtype=np.float32))
+    C = torch.empty((A.n_rows, F), dtype=torch.float32, device="cuda")
+    ws = torch.empty(handle.workspace_bytes(ab.OP_SPMM, A.n_rows, A.nnz, F), dtype=torch.uint8, device="cuda")
+    handle.spmm(A.n_rows, A.n_cols, *d_csr, dev(B, torch), C, F, workspace=ws)
+    torch.cuda.synchronize()
+    As = W.row_slice(A, rows)
+    err = rel_l1_rows(C[torch.from_numpy(rows).cuda()].cpu().numpy(), oracle.spmm(As.rowptr, As.colind, As.val, B))
+    print("config 3, non-negative operands, F=128: plain per-row error max %.2e" % float(err.max()), flush=True)
+    assert err.max() <= 1e-5
+
+
+@pytest.fixture(scope="module")
+def config4(torch):
     A = W.config4_large()
     assert A.n_rows == 2449029 and abs(A.nnz / 123.7e6 - 1) < 0.03
-    d_csr = (dev(A.rowptr, torch), dev(A.colind, torch), dev(A.val, torch))
+    return A, (dev(A.rowptr, torch), dev(A.colind, torch), dev(A.val, torch))
+
+
+@pytest.mark.parametrize("F", [16, 32, 100, 128])
+def test_config4_large_sparse_full_size(torch, ab, handle, config4, F):
+    A, d_csr = config4
     rows = sample_rows(A, 1500, 4)
-    check_spmm(torch, ab, handle, A, d_csr, 100, rows, seed=100)
-    check_sddmm(torch, ab, handle, A, d_csr, 16, rows, seed=16)
-    check_sddmm(torch, ab, handle, A, d_csr, 128, rows, seed=128)
+    check_spmm(torch, ab, handle, A, d_csr, F, rows, seed=F)
+    check_sddmm(torch, ab, handle, A, d_csr, F, rows, seed=F + 1)
+
+
+def test_config4_bf16_operands_and_softmax(torch, ab, handle, config4):
+    A, d_csr = config4
+    rows = sample_rows(A, 1500, 4)
     # bf16 dense operands with fp32 accumulation (the paper's mixed-precision extension), F = 128
     rng = np.random.default_rng(7)
     F = 128

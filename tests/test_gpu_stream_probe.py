@@ -1,5 +1,6 @@
 """The bandwidth-probe kernels move exactly the bytes they claim: read sums every element once, copy
-reproduces the source, the in-place pass halves every element; ragged sizes and bad arguments included."""
+reproduces the source, the in-place pass halves every element, the gather reads every indexed row once; ragged
+sizes and bad arguments included."""
 import numpy as np
 import pytest
 
@@ -45,6 +46,43 @@ def test_stream_probe_rejects_bad_arguments(torch, ab):
                      (7, buf, buf, 64), (ab.STREAM_READ, buf, None, 64)):
             with pytest.raises(ab.AutosageError) as e:
                 h.stream_probe(*args)
+            assert e.value.status == ab.ERR_INVALID_ARG
+    finally:
+        h.close()
+
+
+@pytest.mark.parametrize("row_bytes", [16, 32, 64, 128, 256, 512, 1024])
+@pytest.mark.parametrize("n_idx", [0, 1, 63, 64, 4096 + 17, 300001])
+def test_gather_probe_reads_every_indexed_row_once(torch, ab, row_bytes, n_idx):
+    h = ab.Handle(0)
+    try:
+        n_rows, w = 3001, row_bytes // 4
+        rng = np.random.default_rng(row_bytes + n_idx)
+        host = rng.integers(-4, 5, size=(n_rows, w)).astype(np.float32)      # small integers: fp32 sums are exact
+        idx = rng.integers(0, n_rows, size=n_idx).astype(np.int32)
+        if n_idx > 2:
+            idx[0], idx[-1] = -5, n_rows + 9                                   # out-of-table values are clamped
+        table = torch.from_numpy(host).cuda()
+        d_idx = torch.from_numpy(idx).cuda()
+        sums = torch.full((h.stream_probe_dst_bytes() // 4,), float("nan"), device="cuda")
+        h.gather_probe(table, n_rows, row_bytes, d_idx, sums, n_idx=n_idx)
+        want = float(host[np.clip(idx, 0, n_rows - 1)].astype(np.float64).sum())
+        assert float(sums.double().sum()) == want
+    finally:
+        h.close()
+
+
+def test_gather_probe_rejects_bad_arguments(torch, ab):
+    h = ab.Handle(0)
+    try:
+        table = torch.zeros((16, 32), device="cuda")
+        idx = torch.zeros(8, dtype=torch.int32, device="cuda")
+        sums = torch.zeros(h.stream_probe_dst_bytes() // 4, device="cuda")
+        for args in ((table, 16, 48, idx, sums), (table, 16, 2048, idx, sums), (table, 16, 8, idx, sums),
+                     (table.view(-1)[1:], 15, 128, idx, sums), (table, 0, 128, idx, sums), (table, 16, 128, idx, None),
+                     (None, 16, 128, idx, sums)):
+            with pytest.raises(ab.AutosageError) as e:
+                h.gather_probe(*args)
             assert e.value.status == ab.ERR_INVALID_ARG
     finally:
         h.close()
