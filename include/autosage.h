@@ -127,6 +127,23 @@ autosage_status_t autosage_spmm(autosage_handle_t h, int64_t n_rows, int64_t n_c
                                 autosage_dtype_t dt, const autosage_schedule_t* sched,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or size a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): autosage_spmm with an explicit schedule (sched must not be NULL: the
+ * selector may probe and synchronise) whose hub-split scratch -- partition metadata and per-chunk partial rows,
+ * the `workspace` of autosage_spmm -- is a fixed array of AUTOSAGE_STATIC_SCRATCH_BYTES inside the library's device
+ * image.  Each GPU the library runs on holds that array until the process ends.  Same arguments, results (bit for
+ * bit, for the same schedule) and errors as autosage_spmm; additionally AUTOSAGE_ERR_WORKSPACE_TOO_SMALL when
+ * autosage_workspace_bytes(AUTOSAGE_OP_SPMM, n_rows, nnz, F, 1, sched) exceeds AUTOSAGE_STATIC_SCRATCH_BYTES
+ * (nothing is launched then).  The call allocates and frees nothing, on the device or through any library, and
+ * does not synchronise.  All calls on one GPU share the array, which keeps the previous call's contents (every
+ * word a call reads it has written first, so nothing needs clearing): calls that overlap on one GPU -- two
+ * streams, two handles, two threads -- race on it and must be serialised by the caller. */
+#define AUTOSAGE_STATIC_SCRATCH_BYTES (32u << 20)
+autosage_status_t autosage_spmm_static(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,
+                                       const int32_t* rowptr, const int32_t* colind, const float* val,
+                                       const void* B, int64_t ldb, float* C, int64_t ldc, int32_t F,
+                                       autosage_dtype_t dt, const autosage_schedule_t* sched, void* stream);
+
 /* SDDMM (Notation: A~_ij = <X_i, Y_j> on the pattern of A).  out[p] (fp32, dev, CSR order) for
  * every stored p of row i; X is [n_rows, F], Y is [n_cols, F] (dt, dev).  val is not read
  * (pattern only) and may be NULL.  Same schedule / error rules as autosage_spmm. */

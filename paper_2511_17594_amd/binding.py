@@ -52,6 +52,7 @@ def _load():
         "autosage_set_param": [vp, c.c_char_p, c.c_double],
         "autosage_get_param": [vp, c.c_char_p, c.POINTER(c.c_double)],
         "autosage_spmm": [vp, i64, i64, i64, vp, vp, vp, vp, i64, vp, i64, i32, c.c_int, sp, vp, sz, vp],
+        "autosage_spmm_static": [vp, i64, i64, i64, vp, vp, vp, vp, i64, vp, i64, i32, c.c_int, sp, vp],
         "autosage_sddmm": [vp, i64, i64, i64, vp, vp, vp, vp, i64, vp, i64, i32, c.c_int, vp, sp, vp, sz, vp],
         "autosage_csr_row_softmax": [vp, i64, i64, vp, vp, vp, i32, i32, i32, vp, sz, vp],
         "autosage_csr_attention": [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp, i32, i32, c.c_float, c.c_int, sp, vp, sz, vp],
@@ -99,6 +100,7 @@ _lib, EXPORTED = _load()
 
 
 STREAM_READ, STREAM_COPY, STREAM_INPLACE = 0, 1, 2
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 def status_string(status: int) -> str:
@@ -185,6 +187,14 @@ class Handle:
         _check(_lib.autosage_spmm(self._h, n_rows, n_cols, nnz, _ptr(rowptr), _ptr(colind), _ptr(val), _ptr(B),
                                   F if ldb is None else ldb, _ptr(C), F if ldc is None else ldc, F, dt, _sched(sched),
                                   _ptr(workspace), ws_bytes, _stream(stream)), "autosage_spmm")
+
+    def spmm_static(self, n_rows, n_cols, rowptr, colind, val, B, C, F, sched, dt=F32, stream=None, ldb=None, ldc=None,
+                    nnz=None):
+        """autosage_spmm_static: explicit schedule, scratch in the library's fixed array, nothing allocated."""
+        nnz = int(colind.numel()) if nnz is None else nnz
+        _check(_lib.autosage_spmm_static(self._h, n_rows, n_cols, nnz, _ptr(rowptr), _ptr(colind), _ptr(val), _ptr(B),
+                                         F if ldb is None else ldb, _ptr(C), F if ldc is None else ldc, F, dt, _sched(sched),
+                                         _stream(stream)), "autosage_spmm_static")
 
     def sddmm(self, n_rows, n_cols, rowptr, colind, X, Y, out, F, dt=F32, sched=None, workspace=None, stream=None,
               ldx=None, ldy=None, nnz=None, val=None):

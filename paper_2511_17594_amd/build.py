@@ -20,6 +20,7 @@ SOURCES = [
     "spmm.hip", "spmm_f32.hip", "spmm_bf16.hip", "spmm_f16.hip",
     "sddmm.hip", "sddmm_f32.hip", "sddmm_bf16.hip", "sddmm_f16.hip",
     "attention.hip", "attention_f32.hip", "attention_bf16.hip", "attention_f16.hip", "transpose.hip", "stream_probe.hip",
+    "static_scratch.hip",
 ]
 
 # -packed-fp32-ops is switched off on purpose: packed fp32 instructions are not to be generated.

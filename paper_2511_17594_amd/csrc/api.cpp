@@ -372,6 +372,11 @@ extern "C" autosage_status_t autosage_create(autosage_handle_t* out, int device_
             autosage_destroy(h);
             return AUTOSAGE_ERR_HIP;
         }
+        // the fixed scratch array of autosage_spmm_static: its address on this device (no allocation)
+        if (static_scratch_address(device_id, &h->static_scratch) != AUTOSAGE_OK) {
+            autosage_destroy(h);
+            return AUTOSAGE_ERR_HIP;
+        }
     }
     const char* cp = std::getenv("AUTOSAGE_CACHE");
     if (cp && *cp) {

@@ -100,6 +100,8 @@ struct autosage_ctx {
     // > 0 while the selector times a lower bound of the baseline: the row kernels of the next launches skip
     // rows of at least this many entries and no hub kernel runs (outputs of skipped rows stay untouched)
     int probe_skip_deg = 0;
+    // device address of the library's fixed scratch array on this handle's device (autosage_spmm_static)
+    void* static_scratch = nullptr;
 };
 
 namespace autosage {
@@ -153,6 +155,9 @@ autosage_status_t spmm_entry(autosage_ctx* h, int64_t n_rows, int64_t n_cols, in
                              const int32_t* colind, const float* val, const void* B, int64_t ldb, float* C, int64_t ldc,
                              int32_t F, int dt, const autosage_schedule_t* sched, void* workspace, size_t workspace_bytes,
                              void* stream);
+// Device address of the fixed scratch array on `device` (which must be the current device); looked up once per device.
+autosage_status_t static_scratch_address(int device, void** ptr);
+
 // Checks the 16-byte alignment / width rules of the attention kernels.
 autosage_status_t attention_alignment(const AttnCall& c);
 // Runs the attention pipeline the schedule names (FUSED = single pass, else three stages) on `rows`.
