@@ -32,8 +32,11 @@
  *   - The selector remembers the degree features of the last 16 (rowptr pointer, n_rows, n_cols, nnz)
  *     combinations so that steady-state calls need no device-to-host copy.  Overwriting a rowptr array
  *     in place with another graph of the same sizes therefore replays the old graph's decision (results
- *     stay correct, the schedule may be a poor one); autosage_cache_clear or memoize_signature = 0
- *     drops / disables that memory.
+ *     stay correct, the schedule may be a poor one); autosage_forget_graph drops the memory of one rowptr
+ *     address, autosage_cache_clear or memoize_signature = 0 drop / disable all of it.
+ *   - While `stream` is being captured into a HIP graph a call with sched == NULL succeeds only when it needs
+ *     neither the feature pass nor probes (features remembered and decision cached); otherwise it returns
+ *     AUTOSAGE_ERR_UNSUPPORTED without touching the stream.  Calls with an explicit schedule can be captured.
  */
 #ifndef AUTOSAGE_H
 #define AUTOSAGE_H
@@ -234,7 +237,7 @@ autosage_status_t autosage_narrow_indices(autosage_handle_t h, int64_t n, const 
 
 /* ---- selector -------------------------------------------------------------------------- */
 
-/* Shortlist (Scheduler: "shortlist candidates with a roofline-style estimate").  Host only.
+/* Shortlist (Scheduler subsection: the estimate step that ranks candidates before any probe).  Host only.
  * From the degree histogram and the widths/alignments it ranks the legal schedules of `op` by an
  * estimated time (seconds, ascending) and writes up to max_out of them.  align_bytes is the
  * largest power of two (<= 16) dividing every dense base pointer and every ld * element size. */
@@ -280,6 +283,10 @@ autosage_status_t autosage_last_decision(autosage_handle_t h, char* json_buf, si
 autosage_status_t autosage_cache_load(autosage_handle_t h, const char* path);
 autosage_status_t autosage_cache_save(autosage_handle_t h, const char* path);
 autosage_status_t autosage_cache_clear(autosage_handle_t h);
+/* Drops the remembered degree features of every graph whose rowptr array started at this device address (host
+ * only; the schedule cache, keyed by graph signature, is untouched).  For callers that recycle device memory:
+ * call it when the array at that address is freed or overwritten. */
+autosage_status_t autosage_forget_graph(autosage_handle_t h, const int32_t* rowptr);
 /* Direct access for tests and tools (host only). found = 0/1.  F = feature width (attention: d),
  * H = heads (1 for SpMM / SDDMM). */
 autosage_status_t autosage_cache_lookup(autosage_handle_t h, uint64_t graph_sig, int32_t F, int32_t H,

@@ -70,6 +70,7 @@ def _load():
         "autosage_cache_load": [vp, c.c_char_p],
         "autosage_cache_save": [vp, c.c_char_p],
         "autosage_cache_clear": [vp],
+        "autosage_forget_graph": [vp, vp],
         "autosage_cache_lookup": [vp, c.c_uint64, i32, i32, c.c_int, c.c_int, sp, c.POINTER(i32)],
         "autosage_cache_insert": [vp, c.c_uint64, i32, i32, c.c_int, c.c_int, sp],
         "autosage_decide_attention": [vp, i64, i64, vp, vp, vp, vp, vp, vp, i32, i32, c.c_float, c.c_int, vp, sz, vp, sp],
@@ -366,6 +367,10 @@ class Handle:
 
     def cache_clear(self):
         _check(_lib.autosage_cache_clear(self._h), "autosage_cache_clear")
+
+    def forget_graph(self, rowptr_address: int):
+        """Drops the remembered degree features of the graph whose rowptr started at this device address."""
+        _check(_lib.autosage_forget_graph(self._h, ctypes.c_void_p(int(rowptr_address))), "autosage_forget_graph")
 
     def cache_lookup(self, graph_sig: int, F: int, op: int, dt: int = F32, H: int = 1) -> Optional[Schedule]:
         s, found = Schedule(), ctypes.c_int32()

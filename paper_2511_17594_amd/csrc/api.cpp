@@ -343,7 +343,7 @@ extern "C" autosage_status_t autosage_create(autosage_handle_t* out, int device_
     Params& p = h->params;
     p.alpha = env_double("AUTOSAGE_ALPHA", p.alpha);
     p.probe_frac = env_double("AUTOSAGE_PROBE_FRAC", p.probe_frac);
-    p.probe_iters = (int)env_double("AUTOSAGE_PROBE_ITERS", p.probe_iters);
+    p.probe_iters = std::max(1, (int)env_double("AUTOSAGE_PROBE_ITERS", p.probe_iters));
     p.probe_cap_ms = env_double("AUTOSAGE_PROBE_CAP_MS", p.probe_cap_ms);
     p.probe_topk = (int)env_double("AUTOSAGE_PROBE_TOPK", p.probe_topk);
     p.probe_min_rows = (int)env_double("AUTOSAGE_PROBE_MIN_ROWS", p.probe_min_rows);

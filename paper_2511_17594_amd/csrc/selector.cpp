@@ -262,6 +262,14 @@ extern "C" autosage_status_t autosage_cache_clear(autosage_handle_t h)
     return AUTOSAGE_OK;
 }
 
+extern "C" autosage_status_t autosage_forget_graph(autosage_handle_t h, const int32_t* rowptr)
+{
+    if (!h) return AUTOSAGE_ERR_INVALID_ARG;
+    for (size_t i = h->memo.size(); i-- > 0;)
+        if (h->memo[i].rowptr == rowptr) h->memo.erase(h->memo.begin() + (long)i);
+    return AUTOSAGE_OK;
+}
+
 extern "C" autosage_status_t autosage_cache_lookup(autosage_handle_t h, uint64_t graph_sig, int32_t F, int32_t H,
                                                    autosage_op_t op, autosage_dtype_t dt, autosage_schedule_t* sched,
                                                    int32_t* found)
@@ -544,7 +552,14 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
             }
         }
     }
+    // Neither the feature pass (a device-to-host copy and a wait) nor probes may run on a stream that is being
+    // captured into a graph: such a call is refused before it touches the stream.
+    auto capturing = [&]() {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        return hipStreamIsCapturing(st, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone;
+    };
     if (!have) {
+        if (capturing()) return AUTOSAGE_ERR_UNSUPPORTED;
         int64_t nnz_dev = 0;
         autosage_status_t rc = autosage_graph_features(h, n_rows, n_cols, rowptr, hist, &max_deg, &nnz_dev, &sig, stream);
         if (rc != AUTOSAGE_OK) return rc;
@@ -587,6 +602,7 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
     }
 
     // 3. shortlist
+    if (capturing()) return AUTOSAGE_ERR_UNSUPPORTED;
     const int esize = dtype_bytes(dt);
     int al = common_alignment(dense0, ld0, esize);
     if (op == AUTOSAGE_OP_SDDMM) al = std::min(al, common_alignment(dense1, ld1, esize));

@@ -25,6 +25,11 @@ from . import binding as ab
 
 _handles: Dict[int, ab.Handle] = {}
 _transposes: Dict[Tuple, Tuple] = {}
+# rowptr address -> (its storage, kept alive; the tensor version seen).  The library remembers the degree features of
+# a graph per rowptr address; an entry here pins the storage, so that the address cannot be handed to another graph
+# while the library still remembers it, and records the version, so that an in-place overwrite is noticed.
+_patterns: Dict[int, Tuple] = {}
+_MAX_PATTERNS = 16
 
 
 def handle(device: Optional[torch.device] = None) -> ab.Handle:
@@ -52,6 +57,21 @@ def _dt(t: torch.Tensor) -> int:
 def _check_csr(rowptr, colind):
     if rowptr.dtype != torch.int32 or colind.dtype != torch.int32 or not rowptr.is_cuda or not colind.is_cuda:
         raise TypeError("rowptr and colind must be int32 CUDA tensors")
+    _note_pattern(rowptr)
+
+
+def _note_pattern(rowptr: torch.Tensor):
+    """Keeps the library's per-address memory of degree features in step with the tensors: a rowptr that was
+    overwritten in place is forgotten, and so is the oldest one when more than 16 are pinned."""
+    ptr = rowptr.data_ptr()
+    seen = _patterns.pop(ptr, None)
+    if seen is not None and seen[1] != rowptr._version:
+        handle(rowptr.device).forget_graph(ptr)
+    _patterns[ptr] = (rowptr.untyped_storage(), rowptr._version, rowptr.device)
+    while len(_patterns) > _MAX_PATTERNS:
+        old_ptr = next(iter(_patterns))
+        _, _, dev = _patterns.pop(old_ptr)
+        handle(dev).forget_graph(old_ptr)
 
 
 def csr_indices_int32(rowptr: torch.Tensor, colind: torch.Tensor, n_cols: int):
@@ -95,11 +115,13 @@ def _sddmm(rowptr, colind, X, Y, sched=None, ldx=None, ldy=None, F=None, out=Non
 
 
 def transpose(rowptr: torch.Tensor, colind: torch.Tensor, n_cols: int):
-    """(t_rowptr, t_colind, perm) of the pattern, cached per (storage, version) of the index tensors."""
+    """(t_rowptr, t_colind, perm) of the pattern, cached per (address, version) of the index tensors.  An entry
+    holds the index tensors themselves: while it lives their memory cannot be freed and handed to another pattern
+    of the same size, so an equal key always means the same pattern."""
     key = (rowptr.data_ptr(), colind.data_ptr(), rowptr._version, colind._version, colind.numel(), n_cols)
     hit = _transposes.get(key)
     if hit is not None:
-        return hit
+        return hit[:3]
     h = handle(rowptr.device)
     n_rows, nnz = rowptr.numel() - 1, colind.numel()
     t_rowptr = torch.empty(n_cols + 1, dtype=torch.int32, device=rowptr.device)
@@ -109,8 +131,8 @@ def transpose(rowptr: torch.Tensor, colind: torch.Tensor, n_cols: int):
     h.csr_transpose(n_rows, n_cols, nnz, rowptr, colind, None, t_rowptr, t_colind, None, perm, ws)
     if len(_transposes) >= 8:
         _transposes.pop(next(iter(_transposes)))
-    _transposes[key] = (t_rowptr, t_colind[:nnz], perm[:nnz])
-    return _transposes[key]
+    _transposes[key] = (t_rowptr, t_colind[:nnz], perm[:nnz], rowptr, colind)
+    return _transposes[key][:3]
 
 
 def _gather(perm, values):

@@ -1,5 +1,5 @@
 """The compute calls only enqueue kernels (no allocation, no host synchronisation, no memset), so a
-caller may capture them into a HIP graph.  The graph is replayed several times with fresh inputs
+caller may capture them into a HIP graph; a selector call that would have to probe is refused during capture.  The graph is replayed several times with fresh inputs
 and eager work in between, and every replay is compared bit for bit with the eager result."""
 import numpy as np
 import pytest
@@ -46,6 +46,11 @@ def test_spmm_sddmm_attention_replay_from_a_captured_graph():
         side.synchronize()
         with torch.cuda.graph(g, stream=side):
             work(torch.cuda.current_stream())
+            # a decision that would need probes (SpMM at this width was never decided) is refused while the stream
+            # is being captured, before anything touches the stream: the capture stays valid
+            with pytest.raises(ab.AutosageError) as refused:
+                h.spmm(N, N, rp, ci, va, B, C, F, workspace=ws2, stream=torch.cuda.current_stream())
+            assert refused.value.status == ab.ERR_UNSUPPORTED
     torch.cuda.synchronize()
 
     for rep in range(3):

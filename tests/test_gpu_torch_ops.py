@@ -156,3 +156,63 @@ def test_int64_indices_enter_through_the_narrowing_call(torch, ops, graph):
     empty = ops.csr_indices_int32(torch.zeros(1, dtype=torch.int64, device="cuda"),
                                   torch.zeros(0, dtype=torch.int64, device="cuda"), 5)
     assert empty[0].tolist() == [0] and empty[1].numel() == 0
+
+
+def test_gradients_follow_the_pattern_when_index_memory_is_recycled(torch, ops):
+    """Mini-batches with a fixed fan-out give one pattern after the other with the same number of nonzeros, the
+    first freed before the second is allocated: the transposed-pattern cache and the library's per-address memory of
+    degree features must never hand the second pattern the first one's transpose or features."""
+    import oracle
+    n, fan, F = 600, 8, 16
+    rng = np.random.default_rng(5)
+    seen_ptrs = []
+    for batch in range(3):
+        deg = np.full(n, fan, dtype=np.int64)
+        A = W.csr_from_degrees(rng, deg, n)                      # same rows, columns and nonzeros every time
+        assert A.nnz == n * fan
+        B_h = rng.standard_normal((n, F)).astype(np.float32)
+        Wt_h = rng.standard_normal((n, F)).astype(np.float32)
+        rp, ci = torch.from_numpy(A.rowptr).cuda(), torch.from_numpy(A.colind).cuda()
+        seen_ptrs.append((rp.data_ptr(), ci.data_ptr()))
+        val = torch.from_numpy(A.val).cuda().requires_grad_(True)
+        B = torch.from_numpy(B_h).cuda().requires_grad_(True)
+        C = torch.ops.autosage.spmm_csr(rp, ci, val, B)
+        (C * torch.from_numpy(Wt_h).cuda()).sum().backward()
+        # dL/dB = A^T W through the oracle: SpMM on the oracle's own transpose of this batch's pattern
+        t_rp, t_ci, t_val, _ = oracle.csr_transpose(A.rowptr, A.colind, A.val, n)
+        want_dB = oracle.spmm(t_rp, t_ci, t_val, Wt_h)
+        want_dval = oracle.sddmm(A.rowptr, A.colind, Wt_h, B_h)
+        assert rel(B.grad, torch.from_numpy(want_dB)) <= 1e-5, batch
+        assert rel(val.grad, torch.from_numpy(want_dval)) <= 1e-5, batch
+        del rp, ci, val, B, C                                     # freed before the next batch is allocated
+    # while an entry of either cache lives it pins its index tensors, so no two batches shared an address
+    assert len(set(seen_ptrs)) == len(seen_ptrs)
+
+
+def test_overwritten_rowptr_is_not_replayed(torch, ops):
+    """A rowptr tensor overwritten in place with another graph of the same sizes: the operator notices the new
+    tensor version, the library forgets the address, and the decision carries the new graph's signature."""
+    import oracle
+    n, F = 4096, 32
+    rng = np.random.default_rng(6)
+    deg1 = rng.poisson(6.0, n).astype(np.int64)
+    deg2 = rng.permutation(deg1)                                  # same rows, same nonzeros, another graph
+    deg2[:2] = deg1[:2][::-1] if deg1[0] != deg1[1] else deg2[:2]
+    A1, A2 = W.csr_from_degrees(rng, deg1, n), W.csr_from_degrees(rng, deg2, n)
+    assert A1.nnz == A2.nnz and not np.array_equal(A1.rowptr, A2.rowptr)
+    rp, ci = torch.from_numpy(A1.rowptr).cuda(), torch.from_numpy(A1.colind).cuda()
+    val = torch.from_numpy(A1.val).cuda()
+    B_h = rng.standard_normal((n, F)).astype(np.float32)
+    B = torch.from_numpy(B_h).cuda()
+    h = ops.handle(B.device)
+    C1 = torch.ops.autosage.spmm_csr(rp, ci, val, B)
+    sig1 = h.last_decision()["graph_sig"]
+    assert int(sig1, 16) == oracle.graph_signature(A1.rowptr, n)
+    rp.copy_(torch.from_numpy(A2.rowptr))
+    ci.copy_(torch.from_numpy(A2.colind))
+    val.copy_(torch.from_numpy(A2.val))
+    C2 = torch.ops.autosage.spmm_csr(rp, ci, val, B)
+    sig2 = h.last_decision()["graph_sig"]
+    assert int(sig2, 16) == oracle.graph_signature(A2.rowptr, n) and sig2 != sig1
+    assert rel(C1, torch.from_numpy(oracle.spmm(A1.rowptr, A1.colind, A1.val, B_h))) <= 1e-5
+    assert rel(C2, torch.from_numpy(oracle.spmm(A2.rowptr, A2.colind, A2.val, B_h))) <= 1e-5
