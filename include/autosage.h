@@ -91,13 +91,18 @@ typedef struct {
     int32_t hub_t;         /* rows with degree >= hub_t are split over workgroups; 0 = no hub split */
     int32_t hub_chunk;     /* nonzeros per hub chunk, 64 .. 2^20; 0 = min(hub_t, 2^20) */
     int32_t xcd_remap;     /* 1 = consecutive row blocks stay on one XCD (contiguous row range per L2) */
+    int32_t group_lanes;   /* SDDMM with 16-byte lane loads: lanes that share one gathered dense row per pass, a power of
+                              two; each lane then holds (tile width / 16 bytes) / group_lanes vectors of the row (2, 4 or
+                              8 of them) and the dot product is finished across group_lanes lanes only.  0, or a value
+                              that is not below the lanes one vector per lane would take = one vector per lane.  Any
+                              other operator, mapping or shape with a nonzero value -> AUTOSAGE_ERR_UNSUPPORTED */
 } autosage_schedule_t;
 
 /* ---- lifetime -------------------------------------------------------------------------- */
 
 /* Creates a handle bound to HIP device `device_id` and reads the AUTOSAGE_* environment
  * toggles once (AUTOSAGE_FTILE, AUTOSAGE_WPB, AUTOSAGE_HUB_T, AUTOSAGE_PROBE_FRAC,
- * AUTOSAGE_PROBE_ITERS, AUTOSAGE_PROBE_CAP_MS, AUTOSAGE_PROBE_TOPK, AUTOSAGE_PROBE_MIN_ROWS,
+ * AUTOSAGE_PROBE_ITERS, AUTOSAGE_PROBE_CAP_MS, AUTOSAGE_PROBE_TOPK, AUTOSAGE_PROBE_MIN_ROWS, AUTOSAGE_PROBE_REFINE,
  * AUTOSAGE_ALPHA, AUTOSAGE_CACHE (file loaded now and saved by autosage_destroy),
  * AUTOSAGE_REPLAY_ONLY); the paper's Implementation section names them.
  * device_id < 0 creates a host-only handle: selector, cache and estimate functions work,
@@ -107,7 +112,8 @@ autosage_status_t autosage_destroy(autosage_handle_t h);
 const char* autosage_status_string(autosage_status_t s);
 
 /* Sets a parameter by name.  Selector: "alpha", "probe_frac", "probe_iters", "probe_cap_ms",
- * "probe_topk", "probe_min_rows", "replay_only", "confirm_full", "memoize_signature", "baseline_bound"
+ * "probe_topk", "probe_min_rows", "probe_refine" (most extra probes of the refinement rounds: schedules one knob away
+ * from the best probed one; default 8, 0 = none), "replay_only", "confirm_full", "memoize_signature", "baseline_bound"
  * (1, default: the guardrail's baseline is first bounded from below by timing it without its rows of
  * 1024 entries or more, and timed whole only when that bound does not decide; 0: always timed whole).
  * Row-softmax (forward and backward): "softmax_group" = lanes that share one light row (rounded up to

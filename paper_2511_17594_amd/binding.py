@@ -23,7 +23,7 @@ MAP_PLAIN, MAP_WAVE_ROW, MAP_MULTI_ROW, MAP_FUSED = 0, 1, 2, 3
 
 class Schedule(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("mapping", "f_tile", "waves_per_wg", "vec_bytes", "unroll", "hub_t", "hub_chunk", "xcd_remap")]
+                ("mapping", "f_tile", "waves_per_wg", "vec_bytes", "unroll", "hub_t", "hub_chunk", "xcd_remap", "group_lanes")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}

@@ -80,6 +80,8 @@ autosage_status_t resolve_schedule(const autosage_schedule_t& s, int op, int32_t
     if (r.hub_t > 0 && (r.hub_chunk < kMinHubT || r.hub_chunk > kMaxHubChunk)) return AUTOSAGE_ERR_INVALID_ARG;
     r.xcd_remap = s.xcd_remap ? 1 : 0;
     r.HW = 1;
+    if (s.group_lanes < 0 || s.group_lanes > 64 || (s.group_lanes > 0 && !is_pow2(s.group_lanes))) return AUTOSAGE_ERR_INVALID_ARG;
+    if (s.group_lanes > 0 && op != AUTOSAGE_OP_SDDMM) return AUTOSAGE_ERR_UNSUPPORTED;
 
     // vector width
     int vb = s.vec_bytes;
@@ -165,6 +167,15 @@ autosage_status_t resolve_schedule(const autosage_schedule_t& s, int op, int32_t
             if ((lanes_needed + 63) / 64 > 8) return AUTOSAGE_ERR_UNSUPPORTED;
             r.f_tile = r.G * r.vec * r.K;
             r.tiles = 1;
+        }
+        if (s.group_lanes > 0 && s.group_lanes < r.G) {
+            // narrow groups: the tile's vectors are spread over group_lanes lanes, K of them per lane
+            const int g = s.group_lanes, k = r.G / g;
+            const bool built = (g == 32 && k == 2) || (g == 16 && (k == 2 || k == 4)) || (g == 8 && (k == 2 || k == 4 || k == 8)) ||
+                               (g == 4 && (k == 4 || k == 8));
+            if (heads != 1 || vb != 16 || r.K != 1 || s.mapping != AUTOSAGE_MAP_WAVE_ROW || !built) return AUTOSAGE_ERR_UNSUPPORTED;
+            r.K = k;
+            r.G = g;
         }
         if (heads > 1 && vb == 16 && r.K == 1 && r.G >= 2 && r.G <= 32) {
             int hw = pow2_ceil(heads);
@@ -347,6 +358,7 @@ extern "C" autosage_status_t autosage_create(autosage_handle_t* out, int device_
     p.probe_cap_ms = env_double("AUTOSAGE_PROBE_CAP_MS", p.probe_cap_ms);
     p.probe_topk = (int)env_double("AUTOSAGE_PROBE_TOPK", p.probe_topk);
     p.probe_min_rows = (int)env_double("AUTOSAGE_PROBE_MIN_ROWS", p.probe_min_rows);
+    p.probe_refine = std::max(0, (int)env_double("AUTOSAGE_PROBE_REFINE", p.probe_refine));
     p.replay_only = (int)env_double("AUTOSAGE_REPLAY_ONLY", 0);
     p.force_ftile = (int)env_double("AUTOSAGE_FTILE", 0);
     p.force_wpb = (int)env_double("AUTOSAGE_WPB", 0);
@@ -361,7 +373,7 @@ extern "C" autosage_status_t autosage_create(autosage_handle_t* out, int device_
         (void)hipRuntimeGetVersion(&rt);
         h->cu_count = prop.multiProcessorCount;
         char buf[256];
-        std::snprintf(buf, sizeof buf, "%s_%dcu_hip%d_lib1", prop.gcnArchName, prop.multiProcessorCount, rt);
+        std::snprintf(buf, sizeof buf, "%s_%dcu_hip%d_lib2", prop.gcnArchName, prop.multiProcessorCount, rt);
         h->device_sig = buf;
         for (char& c : h->device_sig)
             if (c == ' ' || c == '\t') c = '_';
@@ -447,6 +459,7 @@ static bool param_access(Params& p, const char* name, double* value, bool set)
     P_DOUBLE("probe_cap_ms", probe_cap_ms)
     P_INT("probe_topk", probe_topk)
     P_INT("probe_min_rows", probe_min_rows)
+    P_INT("probe_refine", probe_refine)
     P_INT("replay_only", replay_only)
     P_INT("confirm_full", confirm_full)
     P_INT("memoize_signature", memoize_signature)
@@ -698,6 +711,7 @@ autosage_status_t exec_attention(autosage_ctx* h, const AttnCall& c, const autos
     s.mapping = AUTOSAGE_MAP_WAVE_ROW;
     s.f_tile = 0;
     s.vec_bytes = 16;
+    s.group_lanes = 0;
     Resolved rs, rp;
     autosage_status_t rc = resolve_schedule(s, AUTOSAGE_OP_SDDMM, d, c.dt, H, 16, 16, &rs);
     if (rc != AUTOSAGE_OK) return rc;

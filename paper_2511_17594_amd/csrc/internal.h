@@ -62,6 +62,7 @@ struct Params {
     double probe_cap_ms = 1.0;
     int probe_topk = 4;
     int probe_min_rows = 16384;
+    int probe_refine = 8;     // most extra probes of the refinement rounds around the best probed schedule (0 = none)
     int replay_only = 0;
     int confirm_full = 1;
     int memoize_signature = 1;
@@ -114,6 +115,7 @@ constexpr int64_t kMaxNnz = (int64_t(1) << 31) - (int64_t(1) << 20);   // most n
 constexpr int kBaselineBoundDeg = 1024;     // rows this long are left out when the selector bounds the baseline from below
 constexpr int kSelectorMinHubT = 512;      // smallest threshold the selector proposes for SpMM / SDDMM
 constexpr int kSelectorMinChunk = 256;     // shortest hub chunk the selector proposes
+constexpr double kRefineGain = 0.97;        // a refinement probe must take at most this share of the best time so far to count
 constexpr double kTileOperandBytes = 96.0 * 1024 * 1024;   // dense operands above this get narrow-tile candidates
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -60,8 +60,8 @@ std::string schedule_json(const autosage_schedule_t& s)
     char buf[256];
     std::snprintf(buf, sizeof buf,
                   "{\"mapping\":%d,\"f_tile\":%d,\"waves_per_wg\":%d,\"vec_bytes\":%d,\"unroll\":%d,\"hub_t\":%d,"
-                  "\"hub_chunk\":%d,\"xcd_remap\":%d}",
-                  s.mapping, s.f_tile, s.waves_per_wg, s.vec_bytes, s.unroll, s.hub_t, s.hub_chunk, s.xcd_remap);
+                  "\"hub_chunk\":%d,\"xcd_remap\":%d,\"group_lanes\":%d}",
+                  s.mapping, s.f_tile, s.waves_per_wg, s.vec_bytes, s.unroll, s.hub_t, s.hub_chunk, s.xcd_remap, s.group_lanes);
     return buf;
 }
 
@@ -167,18 +167,25 @@ void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, in
     // Narrow feature tiles (SpMM, one wavefront per row): the launch walks the tiles one after the other, so a
     // dense operand too large for the caches is worked through in slices of n_cols * tile bytes that fit them,
     // at the price of reading the indices once per tile.  The histogram knows nothing of locality, so these
-    // are ranked by the same estimate and the caller probes the best of each tile width.  (SDDMM accepts an
-    // explicit narrow tile too, one launch per tile, but measured no gain from it, so none is proposed.)
+    // are ranked by the same estimate and the caller probes the best of each tile width.  SDDMM runs a narrow
+    // tile as one launch per tile that adds into the output; that pays only together with narrow lane groups
+    // (the cross-lane reduction is paid once per tile), so its 256-byte tile is proposed with them.
     std::vector<int> ftiles{0};
-    if (op == AUTOSAGE_OP_SPMM && p.force_ftile <= 0 && (int64_t)F * esize >= 512 &&
-        (double)n_cols * F * esize >= kTileOperandBytes) {
+    if (p.force_ftile <= 0 && (int64_t)F * esize >= 512 && (double)n_cols * F * esize >= kTileOperandBytes) {
         ftiles.push_back(256 / esize);
-        ftiles.push_back(512 / esize);
+        if (op == AUTOSAGE_OP_SPMM) ftiles.push_back(512 / esize);
     }
+    // SDDMM lane groups: one vector per lane (0), or a dense row shared by 8 lanes that hold several vectors each
+    // (three cross-lane steps per dot product instead of up to six)
+    std::vector<int> lane_opts{0};
+    if (op == AUTOSAGE_OP_SDDMM) lane_opts.push_back(8);
     for (int mapping = AUTOSAGE_MAP_WAVE_ROW; mapping <= AUTOSAGE_MAP_MULTI_ROW; ++mapping) {
         for (int vb = 16; vb >= esize; vb >>= 1) {
           for (int ft : ftiles) {
             if (ft > 0 && (mapping != AUTOSAGE_MAP_WAVE_ROW || ft >= F || vb < 8)) continue;
+           for (int gl : lane_opts) {
+            if (gl > 0 && (mapping != AUTOSAGE_MAP_WAVE_ROW || vb != 16)) continue;
+            if (op == AUTOSAGE_OP_SDDMM && ft > 0 && gl == 0) continue;
             for (int u : unrolls) {
                 for (int hub : hubs) {
                     if (hub > 0 && max_deg < hub) continue;
@@ -191,14 +198,16 @@ void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, in
                         s.vec_bytes = vb;
                         s.unroll = u;
                         s.hub_t = p.force_hub_t >= 0 ? p.force_hub_t : hub;
-                        // SpMM chunks carry a reduction and a partial row each: four thresholds per chunk amortise
-                        // them; SDDMM chunks are independent, the threshold itself balances best
-                        s.hub_chunk = pick_hub_chunk(hist33, max_deg, s.hub_t, op == AUTOSAGE_OP_SPMM ? 4 : 1,
-                                                     h ? h->cu_count : 0);
+                        // four thresholds per chunk amortise what a chunk costs before its first gather (the search for
+                        // its row, the row's own operand; for SpMM also a reduction and a partial row); fewer where
+                        // the hub rows are too few to occupy the chip with chunks that long
+                        s.hub_chunk = pick_hub_chunk(hist33, max_deg, s.hub_t, 4, h ? h->cu_count : 0);
                         s.xcd_remap = xcd;
+                        s.group_lanes = gl;
                         Resolved r;
                         if (resolve_schedule(s, op, F, dt, 1, align_bytes, align_bytes, &r) != AUTOSAGE_OK) continue;
                         if (r.unroll != u) continue;
+                        if (gl > 0 && r.G != gl) continue;        // the tile is no wider than the group: same kernel as gl = 0
                         double t = estimate_one(m, op, n_rows, nnz, hist33, max_deg, F, esize, r);
                         if (xcd) t *= 1.001;      // no locality information in the histogram: keep it next to its twin
                         // schedules that resolve to the same kernel shape under a smaller unroll are duplicates
@@ -207,6 +216,7 @@ void shortlist(const autosage_ctx* h, int op, int64_t n_rows, int64_t n_cols, in
                     }
                 }
             }
+           }
           }
         }
     }
@@ -290,8 +300,8 @@ extern "C" autosage_status_t autosage_cache_insert(autosage_handle_t h, uint64_t
 }
 
 // One record per line:
-//   autosage-cache-v2 <device_sig> <graph_sig hex> <F> <H> <op> <dt> <mapping> <f_tile> <wpg> <vec_bytes> <unroll>
-//   <hub_t> <hub_chunk> <xcd_remap> <t_baseline_ms> <t_chosen_ms>
+//   autosage-cache-v3 <device_sig> <graph_sig hex> <F> <H> <op> <dt> <mapping> <f_tile> <wpg> <vec_bytes> <unroll>
+//   <hub_t> <hub_chunk> <xcd_remap> <group_lanes> <t_baseline_ms> <t_chosen_ms>
 // Records of another device signature are kept out of the in-memory cache (stale-reuse guard).
 extern "C" autosage_status_t autosage_cache_load(autosage_handle_t h, const char* path)
 {
@@ -306,12 +316,13 @@ extern "C" autosage_status_t autosage_cache_load(autosage_handle_t h, const char
         CacheEntry e{};
         autosage_schedule_t& s = e.sched;
         if (!(ss >> tag >> dev >> sig_hex >> k.F >> k.H >> k.op >> k.dt >> s.mapping >> s.f_tile >> s.waves_per_wg >> s.vec_bytes >>
-              s.unroll >> s.hub_t >> s.hub_chunk >> s.xcd_remap >> e.t_baseline_ms >> e.t_chosen_ms))
+              s.unroll >> s.hub_t >> s.hub_chunk >> s.xcd_remap >> s.group_lanes >> e.t_baseline_ms >> e.t_chosen_ms))
             continue;
-        if (tag != "autosage-cache-v2" || dev != h->device_sig) continue;
+        if (tag != "autosage-cache-v3" || dev != h->device_sig) continue;
         char* end = nullptr;
         k.graph_sig = std::strtoull(sig_hex.c_str(), &end, 16);
         if (end == sig_hex.c_str() || *end != '\0') continue;
+        if (s.group_lanes < 0 || s.group_lanes > 64) continue;
         if (s.mapping < 0 || s.mapping > 3 || k.op < 0 || k.op > 3 || !dtype_known(k.dt) || k.F <= 0 || k.H <= 0) continue;
         h->cache[k] = e;
     }
@@ -329,9 +340,9 @@ extern "C" autosage_status_t autosage_cache_save(autosage_handle_t h, const char
             const CacheKey& k = kv.first;
             const autosage_schedule_t& s = kv.second.sched;
             char buf[512];
-            std::snprintf(buf, sizeof buf, "autosage-cache-v2 %s %016llx %d %d %d %d %d %d %d %d %d %d %d %d %.6f %.6f\n",
+            std::snprintf(buf, sizeof buf, "autosage-cache-v3 %s %016llx %d %d %d %d %d %d %d %d %d %d %d %d %d %.6f %.6f\n",
                           h->device_sig.c_str(), (unsigned long long)k.graph_sig, k.F, k.H, k.op, k.dt, s.mapping, s.f_tile,
-                          s.waves_per_wg, s.vec_bytes, s.unroll, s.hub_t, s.hub_chunk, s.xcd_remap,
+                          s.waves_per_wg, s.vec_bytes, s.unroll, s.hub_t, s.hub_chunk, s.xcd_remap, s.group_lanes,
                           kv.second.t_baseline_ms, kv.second.t_chosen_ms);
             out << buf;
         }
@@ -620,7 +631,7 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
             bool fresh = true;
             for (const autosage_schedule_t& c : cands)
                 if (c.mapping == all[i].mapping && c.hub_t == all[i].hub_t && c.xcd_remap == all[i].xcd_remap &&
-                    c.vec_bytes == all[i].vec_bytes)
+                    c.vec_bytes == all[i].vec_bytes && c.group_lanes == all[i].group_lanes)
                     fresh = false;
             if (fresh) {
                 cands.push_back(all[i]);
@@ -694,23 +705,93 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
     if (!std::isfinite(tb)) return base_rc;
     bool tb_is_bound = can_bound;
     std::vector<double> tc(topk);
-    js << ",\"cache_hit\":false,\"replay_miss\":false,\"probe_rows\":" << sample.count << ",\"probe_stride\":" << stride
-       << ",\"candidates\":[";
-    for (int c = 0; c < topk; ++c) {
+    for (int c = 0; c < topk; ++c)
         tc[c] = time_schedule(h, in, sample, cands[c], workspace, workspace_bytes, st, h->params.probe_iters,
                               h->params.probe_cap_ms);
-        js << (c ? "," : "") << "{\"sched\":" << schedule_json(cands[c]) << ",\"est_ms\":" << num(est[c] * 1e3)
-           << ",\"t_ms\":" << num(tc[c]) << "}";
+
+    // 4b. refinement (SpMM, SDDMM): the estimate ranks from the degree histogram alone, so knobs whose gain is a
+    // cache or tail effect (XCD-aware launch, narrow tiles, narrow lane groups, the split threshold next door) may
+    // be missing from the k above in the combination that wins.  The schedules that differ from the best probed one
+    // in a single knob are probed on the same sample, and once more around the new best when one of them wins.
+    // A neighbour joins the candidate list the decision rule runs over only when it beats the best so far by
+    // kRefineGain: differences of a per cent or two are within the noise of a probe on a row sample, and the knob
+    // left alone is the cheaper guess (the XCD-aware launch costs 1-2 % on a graph without locality).
+    if (op != AUTOSAGE_OP_ATTENTION && h->params.probe_refine > 0) {
+        const bool tile_ok = h->params.force_ftile <= 0 && (int64_t)F * esize >= 512 &&
+                             (double)n_cols * F * esize >= kTileOperandBytes;
+        const int hub_steps[] = {0, 512, 1024, 2048, 4096};
+        auto same = [](const autosage_schedule_t& a, const autosage_schedule_t& b) { return std::memcmp(&a, &b, sizeof a) == 0; };
+        int extra = 0;
+        for (int round = 0; round < 2 && extra < h->params.probe_refine; ++round) {
+            int best = -1;
+            for (size_t c = 0; c < cands.size(); ++c)
+                if (std::isfinite(tc[c]) && (best < 0 || tc[c] < tc[best])) best = (int)c;
+            if (best < 0 || cands[best].mapping != AUTOSAGE_MAP_WAVE_ROW) break;
+            const autosage_schedule_t b = cands[best];
+            std::vector<autosage_schedule_t> nb;
+            autosage_schedule_t s = b;
+            s.xcd_remap = !b.xcd_remap;
+            nb.push_back(s);
+            if (op == AUTOSAGE_OP_SDDMM && b.vec_bytes == 16) {
+                s = b;
+                s.group_lanes = b.group_lanes ? 0 : 8;
+                if (s.group_lanes == 0) s.f_tile = 0;            // the tiled form is only proposed with narrow groups
+                Resolved r;
+                // a tile no wider than the group runs the same kernel as group_lanes = 0: not a neighbour
+                if (resolve_schedule(s, op, F, dt, 1, al, 16, &r) == AUTOSAGE_OK && (s.group_lanes == 0 || r.G == s.group_lanes))
+                    nb.push_back(s);
+            }
+            if (tile_ok && b.vec_bytes >= 8) {
+                s = b;
+                s.f_tile = b.f_tile ? 0 : 256 / esize;
+                if (op == AUTOSAGE_OP_SDDMM && s.f_tile) s.group_lanes = 8;
+                nb.push_back(s);
+            }
+            if (h->params.force_hub_t < 0) {
+                int at = 0;
+                for (int i = 0; i < 5; ++i)
+                    if (hub_steps[i] <= b.hub_t) at = i;
+                for (int i : {at - 1, at + 1}) {
+                    if (i < 0 || i > 4 || (hub_steps[i] > 0 && max_deg < hub_steps[i])) continue;
+                    s = b;
+                    s.hub_t = hub_steps[i];
+                    s.hub_chunk = pick_hub_chunk(hist, max_deg, s.hub_t, 4, h->cu_count);
+                    nb.push_back(s);
+                }
+            }
+            bool improved = false;
+            for (const autosage_schedule_t& cand : nb) {
+                if (extra >= h->params.probe_refine) break;
+                bool seen = false;
+                for (const autosage_schedule_t& c : cands) seen = seen || same(c, cand);
+                if (seen) continue;
+                const double t = time_schedule(h, in, sample, cand, workspace, workspace_bytes, st, h->params.probe_iters,
+                                               h->params.probe_cap_ms);
+                ++extra;
+                if (!std::isfinite(t) || !(t <= kRefineGain * tc[best])) continue;     // no kernel for the shape, or no clear gain
+                cands.push_back(cand);
+                est.push_back(std::numeric_limits<double>::quiet_NaN());
+                tc.push_back(t);
+                improved = true;
+            }
+            if (!improved) break;
+        }
     }
+    const int n_probed = (int)cands.size();
+    js << ",\"cache_hit\":false,\"replay_miss\":false,\"probe_rows\":" << sample.count << ",\"probe_stride\":" << stride
+       << ",\"candidates\":[";
+    for (int c = 0; c < n_probed; ++c)
+        js << (c ? "," : "") << "{\"sched\":" << schedule_json(cands[c]) << ",\"est_ms\":" << num(est[c] * 1e3)
+           << ",\"t_ms\":" << num(tc[c]) << (c >= topk ? ",\"refinement\":true" : "") << "}";
     js << "]";
 
     // 5. guardrail
-    int choice = decide_from_times(topk, tc.data(), tb, h->params.alpha);
+    int choice = decide_from_times(n_probed, tc.data(), tb, h->params.alpha);
     if (choice < 0 && tb_is_bound) {              // the bound rejects everything: ask the baseline itself
         tb = time_baseline(sample, false, h->params.probe_iters, h->params.probe_cap_ms, &base_rc);
         if (!std::isfinite(tb)) return base_rc;
         tb_is_bound = false;
-        choice = decide_from_times(topk, tc.data(), tb, h->params.alpha);
+        choice = decide_from_times(n_probed, tc.data(), tb, h->params.alpha);
     }
     double t_choice = choice >= 0 ? tc[choice] : tb;
     js << ",\"t_baseline_ms\":" << num(tb) << ",\"baseline_light_rows_only\":" << (tb_is_bound ? "true" : "false")
@@ -721,7 +802,27 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
         const RowMap full{0, 1, (int32_t)n_rows, 0};
         // its kernels have run on the sample: up to two timed runs after a warm-up, fewer once 2.5 ms are spent,
         // and a warm-up of 10 ms or more is itself the measurement (large inputs: one run)
-        const double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, 2.5, nullptr, false);
+        double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, 2.5, nullptr, false);
+        // A schedule found by the refinement rounds won on the sample, where a launch is short and latency counts
+        // for more than on the whole input.  It is run off against the best of the ranked candidates on the whole
+        // input (when that one passes the guardrail too) and the faster of the two is kept.
+        std::string runoff;
+        if (choice >= topk) {
+            int best0 = -1;
+            for (int c = 0; c < topk; ++c)
+                if (std::isfinite(tc[c]) && (best0 < 0 || tc[c] < tc[best0])) best0 = c;
+            if (best0 >= 0 && tc[best0] <= h->params.alpha * tb) {
+                const double tf_0 = time_schedule(h, in, full, cands[best0], workspace, workspace_bytes, st, 2, 2.5, nullptr, false);
+                const bool switched = tf_0 < tf_c;
+                runoff = ",\"runoff\":{\"index\":" + std::to_string(best0) + ",\"t_ms\":" + num(tf_0) + ",\"t_refined_ms\":" +
+                         num(tf_c) + ",\"switched\":" + (switched ? "true" : "false") + "}";
+                if (switched) {
+                    choice = best0;
+                    t_choice = tc[best0];
+                    tf_c = tf_0;
+                }
+            }
+        }
         // Lower bounds of the baseline on the whole input, cheapest first: its time on the sample (a subset of
         // the rows), then its rows below 8 * kBaselineBoundDeg entries on the whole input (the longest of them
         // still costs one wavefront well under a millisecond).  When a bound already covers the choice's time the
@@ -736,7 +837,7 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
         const bool demote = !(tf_c <= tf_b);
         js << ",\"confirm\":{\"t_choice_ms\":" << num(tf_c) << ",\"t_baseline_ms\":" << num(tf_b)
            << ",\"baseline_bound_only\":" << (bound_settles ? "true" : "false") << ",\"demoted\":"
-           << (demote ? "true" : "false") << "}";
+           << (demote ? "true" : "false") << runoff << "}";
         if (demote) {
             choice = -1;
             t_choice = tb;

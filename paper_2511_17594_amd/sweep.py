@@ -97,8 +97,11 @@ def main(argv=None):
 
     def short(c):
         m = {0: "plain", 1: "wave-row", 2: "multi-row"}[c["mapping"]]
-        return "%s v%d u%d hub %d%s%s" % (m, c["vec_bytes"], c["unroll"], c["hub_t"],
-                                          " tile %d" % c["f_tile"] if c["f_tile"] else "", " xcd" if c["xcd_remap"] else "")
+        return "%s v%d u%d hub %d%s%s%s%s" % (m, c["vec_bytes"], c["unroll"], c["hub_t"],
+                                              "/%d" % c["hub_chunk"] if c["hub_t"] else "",
+                                              " tile %d" % c["f_tile"] if c["f_tile"] else "",
+                                              " lanes %d" % c["group_lanes"] if c.get("group_lanes") else "",
+                                              " xcd" if c["xcd_remap"] else "")
 
     if args.attention:
         if N != M:

@@ -144,6 +144,54 @@ def test_sddmm_f32_schedules(torch, handle, ab, skew_graph, F):
     assert ran >= 5
 
 
+@pytest.mark.parametrize("kind,F", [("f32", 32), ("f32", 64), ("f32", 100), ("f32", 128), ("f32", 256), ("f32", 36),
+                                     ("bf16", 64), ("bf16", 128), ("bf16", 256), ("bf16", 512), ("f16", 128)])
+def test_sddmm_narrow_lane_groups(torch, handle, ab, skew_graph, kind, F):
+    """SDDMM with a dense row shared by fewer lanes (each holding several 16-byte vectors): every group size that has
+    kernels for the width, with and without hub split and narrow feature tiles, against the oracle; shapes without
+    kernels are refused, and so is the knob on SpMM."""
+    A = skew_graph
+    rng = np.random.default_rng(1500 + F)
+    X = rng.standard_normal((A.n_rows, F)).astype(np.float32)
+    Y = rng.standard_normal((A.n_cols, F)).astype(np.float32)
+    if kind == "bf16":
+        X, Y = (W.float_to_bf16_bits(t).reshape(t.shape) for t in (X, Y))
+        absf = lambda t: t & np.uint16(0x7FFF)
+    elif kind == "f16":
+        X, Y = X.astype(np.float16), Y.astype(np.float16)
+        absf = np.abs
+    else:
+        absf = np.abs
+    ref = oracle.sddmm(A.rowptr, A.colind, X, Y)
+    ref_abs = oracle.sddmm(A.rowptr, A.colind, absf(X), absf(Y))
+    vec = 4 if kind == "f32" else 8
+    ran = 0
+    for lanes in (4, 8, 16, 32):
+        for kw in (dict(), dict(hub_t=256, hub_chunk=512, xcd_remap=1), dict(f_tile=256 // (16 // vec), hub_t=128, unroll=2)):
+            s = sched_of(ab, mapping=1, group_lanes=lanes, **kw)
+            tile = min(kw.get("f_tile", F), F)
+            full = 1                                           # lanes one vector per lane would take for the tile
+            while full * vec < tile:
+                full *= 2
+            k = full // lanes if lanes < full else 1
+            legal = F % vec == 0 and (lanes >= full or (full <= 64 and (lanes, k) in
+                                                      ((32, 2), (16, 2), (16, 4), (8, 2), (8, 4), (8, 8), (4, 4), (4, 8))))
+            try:
+                out = run_sddmm(torch, handle, ab, A, X, Y, s)
+            except ab.AutosageError as e:
+                assert e.status == ab.ERR_UNSUPPORTED and not legal, (kind, F, lanes, kw, str(e))
+                continue
+            assert legal, (kind, F, lanes, kw)
+            ran += 1
+            assert np.isfinite(out).all(), (lanes, kw)
+            err = rel_l1_segments(out, ref, A.rowptr, ref_abs, terms=F)
+            assert err.max() <= (TOL_F32 if kind == "f32" else 1e-4), (kind, F, lanes, kw, float(err.max()))
+    assert ran >= (3 if F % vec == 0 else 0)
+    with pytest.raises(ab.AutosageError) as e:                  # the knob belongs to SDDMM
+        run_spmm(torch, handle, ab, A, Y, sched_of(ab, mapping=1, group_lanes=8))
+    assert e.value.status == ab.ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("half", ["bf16", "f16"])
 @pytest.mark.parametrize("F", [8, 30, 64, 128, 520])
 def test_spmm_sddmm_bf16_operands(torch, handle, ab, skew_graph, F, half):

@@ -61,14 +61,25 @@ def test_decide_probe_guardrail_cache_replay(torch, ab, graph, tmp_path):
     d1 = h.last_decision()
     assert d1["cache_hit"] is False and d1["replay_miss"] is False
     assert d1["graph_sig"] == "%016x" % oracle.graph_signature(A.rowptr, A.n_cols)
-    assert 1 <= len(d1["candidates"]) <= 4 and d1["probe_rows"] >= 512
-    keys = [(c["sched"]["mapping"], c["sched"]["hub_t"], c["sched"]["xcd_remap"], c["sched"]["vec_bytes"]) for c in d1["candidates"]]
-    assert len(set(keys)) == len(keys)                       # the probed candidates differ in more than the unroll depth
+    ranked = [c for c in d1["candidates"] if not c.get("refinement")]
+    refined = [c for c in d1["candidates"] if c.get("refinement")]
+    assert 1 <= len(ranked) <= 4 and len(refined) <= 8 and d1["probe_rows"] >= 512
+    assert d1["candidates"][:len(ranked)] == ranked                          # the refinement rounds come after the ranked k
+    keys = [(c["sched"]["mapping"], c["sched"]["hub_t"], c["sched"]["xcd_remap"], c["sched"]["vec_bytes"]) for c in ranked]
+    assert len(set(keys)) == len(keys)                       # the ranked candidates differ in more than the unroll depth
+    scheds = [tuple(sorted(c["sched"].items())) for c in d1["candidates"]]
+    assert len(set(scheds)) == len(scheds)                   # no schedule is probed twice
     t = [c["t_ms"] if c["t_ms"] is not None else float("inf") for c in d1["candidates"]]
     assert d1["choice_index"] == oracle.decide(t, d1["t_baseline_ms"], d1["alpha"])
     if d1["choice_index"] >= 0 and not d1.get("confirm", {}).get("demoted", False):
-        assert d1["choice"] == d1["candidates"][d1["choice_index"]]["sched"]
-        assert t[d1["choice_index"]] <= d1["alpha"] * d1["t_baseline_ms"]       # Proposition 1 on the probe times
+        # the rule's pick, unless the full-input run-off put the best ranked candidate back in front of a refined one
+        runoff = d1.get("confirm", {}).get("runoff", {})
+        kept = runoff["index"] if runoff.get("switched") else d1["choice_index"]
+        assert d1["choice"] == d1["candidates"][kept]["sched"]
+        assert t[kept] <= d1["alpha"] * d1["t_baseline_ms"]                     # Proposition 1 on the probe times
+        if runoff:
+            assert d1["candidates"][d1["choice_index"]].get("refinement") and not d1["candidates"][runoff["index"]].get("refinement")
+            assert runoff["switched"] is (runoff["t_ms"] < runoff["t_refined_ms"])
     else:
         assert d1["choice"]["mapping"] == ab.MAP_PLAIN
 

@@ -173,7 +173,7 @@ def test_cache_round_trip_and_corrupt_file(ab, host, tmp_path):
         f.write(lines[0][: len(lines[0]) // 2] + "\n")
         f.write(lines[0].replace(" host ", " some_other_gpu ") + "\n")
         f.write(lines[1] + "\n")
-        f.write(lines[1].replace("autosage-cache-v2", "autosage-cache-v1") + "\n")      # records of an older schema are skipped
+        f.write(lines[1].replace("autosage-cache-v3", "autosage-cache-v2") + "\n")      # records of an older schema are skipped
     h3 = ab.Handle(-1)
     h3.cache_load(path)
     found = [h3.cache_lookup(0xDEADBEEF12345678, 64, ab.OP_SPMM, ab.F32), h3.cache_lookup(42, 128, ab.OP_SDDMM, ab.BF16)]
@@ -205,7 +205,7 @@ def test_env_toggles_are_read_at_creation(ab, monkeypatch, tmp_path):
     assert c and all(s.hub_t == 2048 for s, _ in c)
     h.cache_insert(7, 64, ab.OP_SPMM, ab.F32, ab.baseline_schedule())
     h.close()                                               # AUTOSAGE_CACHE is written on destroy
-    assert os.path.exists(path) and "autosage-cache-v2" in open(path).read()
+    assert os.path.exists(path) and "autosage-cache-v3" in open(path).read()
 
 
 def test_size_limits_are_checked_before_anything_else(ab, host):
