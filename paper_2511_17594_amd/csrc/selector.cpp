@@ -663,6 +663,21 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
                 est.push_back(all_est[i]);
                 have_three = true;
             }
+            // K and V larger than the Infinity Cache: the best-ranked single pass also runs with the heads walked in
+            // two tiles (each tile gathers from half of K and V).  What that gains is a cache effect of the whole
+            // input, so the two forms are run off there (step 6), not on the sample.
+            if (h->params.force_ftile <= 0 && in.H % 2 == 0 && 2.0 * (double)n_cols * in.H * F * esize > kHeadTileOperandBytes) {
+                for (size_t i = 0; i < cands.size(); ++i) {
+                    if (cands[i].mapping != AUTOSAGE_MAP_FUSED || cands[i].f_tile != 0) continue;
+                    autosage_schedule_t tiled = cands[i];
+                    tiled.f_tile = (in.H / 2) * F;
+                    AttnShape shape{};
+                    if (!attn_fused_shape_tiled(in.H, F, dt, in.H / 2, &shape)) break;
+                    cands.push_back(tiled);
+                    est.push_back(est[i]);
+                    break;
+                }
+            }
         }
     }
     const int topk = (int)cands.size();
@@ -807,7 +822,29 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
         // for more than on the whole input.  It is run off against the best of the ranked candidates on the whole
         // input (when that one passes the guardrail too) and the faster of the two is kept.
         std::string runoff;
-        if (choice >= topk) {
+        if (op == AUTOSAGE_OP_ATTENTION && cands[choice].mapping == AUTOSAGE_MAP_FUSED) {
+            // the same single pass with and without head tiles: the tiled form must win by kRefineGain on the whole
+            // input to be kept, the untiled one takes over from a tiled choice whenever it is faster there
+            for (int c = 0; c < n_probed; ++c) {
+                autosage_schedule_t twin = cands[c];
+                twin.f_tile = cands[choice].f_tile;
+                if (c == choice || cands[c].f_tile == cands[choice].f_tile || std::memcmp(&twin, &cands[choice], sizeof twin) != 0)
+                    continue;
+                if (!(tc[c] <= h->params.alpha * tb)) break;
+                const double tf_t = time_schedule(h, in, full, cands[c], workspace, workspace_bytes, st, 2, 2.5, nullptr, false);
+                const bool to_tiled = cands[c].f_tile != 0;
+                const bool switched = to_tiled ? tf_t <= kRefineGain * tf_c : tf_t < tf_c;
+                runoff = ",\"runoff\":{\"index\":" + std::to_string(c) + ",\"t_ms\":" + num(tf_t) + ",\"t_refined_ms\":" +
+                         num(tf_c) + ",\"head_tiles\":true,\"switched\":" + (switched ? "true" : "false") + "}";
+                if (switched) {
+                    choice = c;
+                    t_choice = tc[c];
+                    tf_c = tf_t;
+                }
+                break;
+            }
+        }
+        if (choice >= topk && op != AUTOSAGE_OP_ATTENTION) {
             int best0 = -1;
             for (int c = 0; c < topk; ++c)
                 if (std::isfinite(tc[c]) && (best0 < 0 || tc[c] < tc[best0])) best0 = c;
