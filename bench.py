@@ -224,15 +224,20 @@ def main():
     dom = max(per_stage, key=lambda k: per_stage[k]["avg_ms"] * per_stage[k]["launches_per_step"])
     # HBM traffic of the dominant kernel: rocprofv3 counters cannot be read from inside this process, so the figure is
     # the committed one of the same command (profiles/bench_hbm_traffic.txt names the summary it comes from)
+    # (each line: stage, bytes per launch, the schedule of the call the stage belongs to; a figure recorded for
+    # another schedule than the one this run's selector chose is not reported)
     traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", "bench_hbm_traffic.txt")
+    dom_call = dom.split(".")[0] + "." + ("attention" if dom.split(".")[1].startswith(("attn", "softmax")) else
+                                          "sddmm" if dom.split(".")[1].startswith("sddmm") else "spmm")
     if os.path.exists(tpath):
         for ln in open(tpath):
-            parts = ln.split()
+            parts = ln.split(None, 2)
             if ln.startswith("# source:"):
                 traffic_source = ln[len("# source:"):].strip()
-            elif len(parts) == 2 and parts[0] == dom and parts[1].isdigit():
-                traffic = int(parts[1])
+            elif len(parts) == 3 and parts[0] == dom and parts[1].isdigit():
+                if json.loads(parts[2]) == decisions.get(dom_call, {}).get("choice"):
+                    traffic = int(parts[1])
     roofline = {"bound": "hbm", "kernel": dom, "achieved": per_stage[dom]["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": per_stage[dom]["gbs"] / HBM_PEAK_GBS, "traffic": traffic,
                 "traffic_source": None if traffic is None else

@@ -218,4 +218,16 @@ __device__ __forceinline__ int xcd_contiguous_block(int launched_id, int n_launc
     return (launched_id & 7) * per + (launched_id >> 3);
 }
 
+// The same for a launch padded beyond the n real work items (hub chunks: the grid covers a host-side upper bound,
+// the true count is read on the device): every XCD walks one contiguous eighth of [0, n).  Returns -1 for an idle
+// workgroup.  The grid must hold at least 8 * ceil(n / 8) workgroups.
+__device__ __forceinline__ int xcd_contiguous_item(int launched_id, int n)
+{
+    const int per = (n + 7) >> 3;
+    const int q = launched_id >> 3;
+    if (q >= per) return -1;
+    const int item = (launched_id & 7) * per + q;
+    return item < n ? item : -1;
+}
+
 }  // namespace autosage

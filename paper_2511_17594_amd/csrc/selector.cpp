@@ -663,21 +663,6 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
                 est.push_back(all_est[i]);
                 have_three = true;
             }
-            // K and V larger than the Infinity Cache: the best-ranked single pass also runs with the heads walked in
-            // two tiles (each tile gathers from half of K and V).  What that gains is a cache effect of the whole
-            // input, so the two forms are run off there (step 6), not on the sample.
-            if (h->params.force_ftile <= 0 && in.H % 2 == 0 && 2.0 * (double)n_cols * in.H * F * esize > kHeadTileOperandBytes) {
-                for (size_t i = 0; i < cands.size(); ++i) {
-                    if (cands[i].mapping != AUTOSAGE_MAP_FUSED || cands[i].f_tile != 0) continue;
-                    autosage_schedule_t tiled = cands[i];
-                    tiled.f_tile = (in.H / 2) * F;
-                    AttnShape shape{};
-                    if (!attn_fused_shape_tiled(in.H, F, dt, in.H / 2, &shape)) break;
-                    cands.push_back(tiled);
-                    est.push_back(est[i]);
-                    break;
-                }
-            }
         }
     }
     const int topk = (int)cands.size();
@@ -790,6 +775,28 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
                 improved = true;
             }
             if (!improved) break;
+        }
+    }
+    // Attention with K and V larger than the Infinity Cache: the fastest single pass of the sample is also probed with
+    // the heads walked in two tiles (each tile gathers from half of K and V).  What that gains is a cache effect of
+    // the whole input, so the two forms are run off there (step 6) whatever the sample says.
+    if (op == AUTOSAGE_OP_ATTENTION && h->params.force_ftile <= 0 && in.H % 2 == 0 &&
+        2.0 * (double)n_cols * in.H * F * esize > kHeadTileOperandBytes) {
+        int best = -1;
+        for (int c = 0; c < topk; ++c)
+            if (cands[c].mapping == AUTOSAGE_MAP_FUSED && cands[c].f_tile == 0 && std::isfinite(tc[c]) && (best < 0 || tc[c] < tc[best]))
+                best = c;
+        AttnShape shape{};
+        if (best >= 0 && attn_fused_shape_tiled(in.H, F, dt, in.H / 2, &shape)) {
+            autosage_schedule_t tiled = cands[best];
+            tiled.f_tile = (in.H / 2) * F;
+            const double t = time_schedule(h, in, sample, tiled, workspace, workspace_bytes, st, h->params.probe_iters,
+                                           h->params.probe_cap_ms);
+            if (std::isfinite(t)) {
+                cands.push_back(tiled);
+                est.push_back(est[best]);
+                tc.push_back(t);
+            }
         }
     }
     const int n_probed = (int)cands.size();

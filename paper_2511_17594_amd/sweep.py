@@ -63,6 +63,12 @@ def main(argv=None):
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16", "f16"], help="element type of the dense input operands")
     ap.add_argument("--softmax", action="store_true", help="row-softmax forward / backward table instead of SpMM / SDDMM")
     ap.add_argument("--attention", action="store_true", help="CSR attention (forward and backward) table instead of SpMM / SDDMM")
+    ap.add_argument("--schedule", action="append", default=[],
+                    help="run this explicit schedule instead of the selector's choice, e.g. mapping=1,hub_t=512,hub_chunk=2048,"
+                         "group_lanes=8 (fields of autosage_schedule_t; may be given several times: one table row each)")
+    ap.add_argument("--no-fallback", action="store_true", help="do not time the guardrail's fallback kernel")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run a plain 1 GiB device-to-device copy three times (known traffic for profiler counter scaling)")
     args = ap.parse_args(argv)
 
     import torch
@@ -81,6 +87,14 @@ def main(argv=None):
     h = ab.Handle(0)
     stream = torch.cuda.current_stream()
     base = ab.baseline_schedule()
+    explicit = [ab.Schedule(**{k: int(v) for k, v in (kv.split("=") for kv in text.split(","))}) for text in args.schedule]
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)                  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     def timed(fn, iters):
         fn()
@@ -209,17 +223,22 @@ def main(argv=None):
             ops.append(("SDDMM", lambda s: h.sddmm(N, M, rp, ci, X, B, out, F, dt=dt, sched=s, workspace=ws, stream=stream,
                                                    nnz=nnz)))
         for name, fn in ops:
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            fn(None)
-            torch.cuda.synchronize()
-            cold = (time.perf_counter() - t0) * 1e3
-            choice = h.last_decision().get("choice")
-            t = timed(lambda: fn(None), args.iters)
-            tb = timed(lambda: fn(base), 3)
-            print("| %s | %d | %.3f | %.0f | %.0f | %.0f %% | %.0f | %.3f | %.2fx | %.1f | %s |"
-                  % (name, F, t, 2.0 * nnz * F / t / 1e6, bg / t / 1e6, 100 * bg / t / 1e6 / HBM_PEAK_GBS, bmin[name] / t / 1e6,
-                     tb, tb / t, cold, short(choice)), flush=True)
+            for sched in explicit or [None]:
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                try:
+                    fn(sched)
+                except ab.AutosageError as e:
+                    print("| %s | %d | | | | | | | | | refused: %s |" % (name, F, short(sched.as_dict())), flush=True)
+                    continue
+                torch.cuda.synchronize()
+                cold = (time.perf_counter() - t0) * 1e3
+                choice = h.last_decision().get("choice") if sched is None else sched.as_dict()
+                t = timed(lambda: fn(sched), args.iters)
+                tb = float("nan") if args.no_fallback else timed(lambda: fn(base), 3)
+                print("| %s | %d | %.3f | %.0f | %.0f | %.0f %% | %.0f | %.3f | %.2fx | %.1f | %s%s |"
+                      % (name, F, t, 2.0 * nnz * F / t / 1e6, bg / t / 1e6, 100 * bg / t / 1e6 / HBM_PEAK_GBS, bmin[name] / t / 1e6,
+                         tb, tb / t, cold, "" if sched is None else "given: ", short(choice)), flush=True)
         if args.vendor and args.dtype == "f32":
             try:
                 from . import vendor
