@@ -209,6 +209,26 @@ template <int G> __device__ __forceinline__ float across_groups_sum(float x)
     return x;
 }
 
+// Largest k in [0, n) with ptr[k] <= x (ptr ascending, ptr[0] <= x), found by the whole wavefront together: every
+// round the 64 lanes probe 64 evenly spaced entries of the remaining range with one load instruction and a ballot
+// picks the interval, so a table of n entries takes ceil(log64 n) dependent loads (three for 262 144) where a
+// scalar binary search takes log2 n.  All 64 lanes must call it with the same arguments; all get the result.
+__device__ __forceinline__ int wave_upper_slot(const int32_t* __restrict__ ptr, int n, int x)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    int lo = 0, hi = n;                              // answer in [lo, hi), ptr[lo] <= x
+    while (hi - lo > 1) {
+        const int step = (hi - lo + kWave - 1) / kWave;
+        const int idx = lo + lane * step;
+        const bool le = idx < hi && ptr[idx] <= x;   // true for a prefix of the lanes (lane 0 included)
+        const unsigned long long m = __ballot(le);
+        const int j = 63 - __clzll((long long)m);
+        lo += j * step;
+        hi = min(hi, lo + step);
+    }
+    return __builtin_amdgcn_readfirstlane(lo);
+}
+
 // Maps a launched block id to a logical block id so that each of the 8 XCDs (hardware
 // dispatches consecutive workgroup ids round-robin over them) walks one contiguous eighth of
 // the logical range.  The grid must be padded to a multiple of 8; ids >= n_logical are idle.

@@ -142,16 +142,6 @@ __global__ void __launch_bounds__(1024) softmax_rows_kernel(SoftmaxDev a)
     }
 }
 
-__device__ __forceinline__ int softmax_upper_slot(const int32_t* __restrict__ ptr, int n, int x)
-{
-    int lo = 0, hi = n;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (ptr[mid] <= x) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
 // One workgroup per chunk: (max, sum) of the chunk's scores for every head.
 __global__ void __launch_bounds__(1024) softmax_hub_partial_kernel(SoftmaxDev a)
 {
@@ -162,7 +152,7 @@ __global__ void __launch_bounds__(1024) softmax_hub_partial_kernel(SoftmaxDev a)
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int wpg = blockDim.x >> 6;
-    const int k_hub = softmax_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
+    const int k_hub = wave_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
     const int row = row_of(a.rows, a.hub_rows[k_hub]);
     const int t = chunk - a.chunk_ptr[k_hub];
     const int q0 = a.rowptr[row] + t * a.hub_chunk;
@@ -244,7 +234,7 @@ __global__ void __launch_bounds__(1024) softmax_hub_normalise_kernel(SoftmaxDev 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int wpg = blockDim.x >> 6;
-    const int k_hub = softmax_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
+    const int k_hub = wave_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
     const int row = row_of(a.rows, a.hub_rows[k_hub]);
     const int c0 = a.chunk_ptr[k_hub];
     const int t = chunk - c0;
@@ -328,7 +318,7 @@ __global__ void __launch_bounds__(1024) softmax_bwd_hub_partial_kernel(SoftmaxBw
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int wpg = blockDim.x >> 6;
-    const int k_hub = softmax_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
+    const int k_hub = wave_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
     const int row = row_of(a.rows, a.hub_rows[k_hub]);
     const int t = chunk - a.chunk_ptr[k_hub];
     const int q0 = a.rowptr[row] + t * a.hub_chunk;
@@ -392,7 +382,7 @@ __global__ void __launch_bounds__(1024) softmax_bwd_hub_apply_kernel(SoftmaxBwdD
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int wpg = blockDim.x >> 6;
-    const int k_hub = softmax_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
+    const int k_hub = wave_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
     const int row = row_of(a.rows, a.hub_rows[k_hub]);
     const int c0 = a.chunk_ptr[k_hub];
     const int t = chunk - c0;
@@ -774,7 +764,7 @@ struct ChunkSpan {
 template <int VEC, typename Dev>
 __device__ __forceinline__ ChunkSpan chunk_span(const Dev& a, int chunk)
 {
-    const int k_hub = softmax_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
+    const int k_hub = wave_upper_slot(a.chunk_ptr, a.counts->n_hub, chunk);
     const int row = row_of(a.rows, a.hub_rows[k_hub]);
     ChunkSpan s;
     s.c0 = a.chunk_ptr[k_hub];
