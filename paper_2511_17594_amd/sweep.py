@@ -17,6 +17,13 @@ Workloads: config1..4 (the benchmark configurations), er (Erdos-Renyi N = 200000
 the paper's extreme-sparsity stressor) and hubsplit_5k / hubsplit_12k (N = 20000, a few rows of degree
 5000 / 12000, the rest 64 / 32: the shape of the paper's split-versus-baseline table; the number of hub
 rows is not given there, 32 is used).
+`--column-slices S` measures what processing the pattern in S column ranges would cost, with the library's own
+kernels: the pattern is cut on the host into S patterns that hold the nonzeros of one column range each (so the
+slice of the gathered operand a launch touches is 1/S of it and can stay in the Infinity Cache), every slice is
+decided by the selector on its own, and the S launches are timed back to back beside the unsliced call.  For SDDMM
+that is the whole sliced operation (every nonzero is written once either way); for SpMM and the single-pass
+attention it leaves out the merge of the S partial results per row, so the figure is a lower bound of the sliced
+form's time.
 """
 from __future__ import annotations
 
@@ -69,6 +76,8 @@ def main(argv=None):
     ap.add_argument("--no-fallback", action="store_true", help="do not time the guardrail's fallback kernel")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device-to-device copy three times (known traffic for profiler counter scaling)")
+    ap.add_argument("--column-slices", type=int, default=0,
+                    help="time the pattern cut into this many column ranges, one launch per range, beside the unsliced call")
     args = ap.parse_args(argv)
 
     import torch
@@ -116,6 +125,66 @@ def main(argv=None):
                                               " tile %d" % c["f_tile"] if c["f_tile"] else "",
                                               " lanes %d" % c["group_lanes"] if c.get("group_lanes") else "",
                                               " xcd" if c["xcd_remap"] else "")
+
+    def column_slices(S):
+        """The S patterns that hold the nonzeros of one column range each, as device CSR arrays."""
+        rows = np.repeat(np.arange(N, dtype=np.int32), deg)
+        out = []
+        for k in range(S):
+            lo, hi = (M * k) // S, (M * (k + 1)) // S
+            keep = (A.colind >= lo) & (A.colind < hi)
+            rp_k = np.zeros(N + 1, dtype=np.int64)
+            np.cumsum(np.bincount(rows[keep], minlength=N), out=rp_k[1:])
+            out.append((int(keep.sum()), torch.from_numpy(rp_k.astype(np.int32)).cuda(), torch.from_numpy(A.colind[keep]).cuda(),
+                        torch.from_numpy(A.val[keep]).cuda()))
+        return out
+
+    if args.column_slices > 1:
+        S = args.column_slices
+        parts = column_slices(S)
+        print("| op | F | column ranges | gathered operand per range MB | unsliced ms | sliced ms | sliced / unsliced | what the sliced figure leaves out |")
+        print("|---|---|---|---|---|---|---|---|")
+        if args.attention:
+            H, d = 8, 64
+            half = torch.float16 if args.dtype == "f16" else torch.bfloat16
+            in_dt = ab.F16 if args.dtype == "f16" else ab.BF16
+            g = torch.Generator(device="cuda").manual_seed(5)
+            Q, K, V = (torch.randn((N, H, d), device="cuda", generator=g).mul_(d ** -0.25).to(half) for _ in range(3))
+            O = torch.empty((N, H, d), device="cuda")
+            ws = torch.empty(h.workspace_bytes(ab.OP_ATTENTION, N, nnz, d, H), dtype=torch.uint8, device="cuda")
+            call = lambda n_k, rp_k, ci_k: h.csr_attention(N, rp_k, ci_k, Q, K, V, O, H, d, d ** -0.5, in_dt=in_dt, workspace=ws,
+                                                           stream=stream, nnz=n_k)
+            t_full = timed(lambda: call(nnz, rp, ci), args.iters)
+            t_cut = timed(lambda: [call(n_k, rp_k, ci_k) for n_k, rp_k, ci_k, _ in parts], args.iters)
+            print("| attention (H = %d, d = %d, %s) | %d | %d | %.0f | %.3f | %.3f | %.2f | merging S running-softmax states per row |"
+                  % (H, d, "f16" if args.dtype == "f16" else "bf16", H * d, S, 2.0 * N * H * d * 2 / S / 1e6, t_full, t_cut,
+                     t_cut / t_full), flush=True)
+            h.close()
+            return
+        dt = {"f32": ab.F32, "bf16": ab.BF16, "f16": ab.F16}[args.dtype]
+        esz = 4 if args.dtype == "f32" else 2
+        for F in widths:
+            g = torch.Generator(device="cuda").manual_seed(F)
+            B = torch.randn((M, F), device="cuda", generator=g)
+            X = torch.randn((N, F), device="cuda", generator=g)
+            if args.dtype != "f32":
+                half = torch.bfloat16 if args.dtype == "bf16" else torch.float16
+                B, X = B.to(half), X.to(half)
+            C = torch.empty((N, F), device="cuda")
+            out = torch.empty(max(nnz, 1), device="cuda")
+            ws = torch.empty(h.workspace_bytes(ab.OP_SPMM, N, nnz, F), dtype=torch.uint8, device="cuda")
+            spmm = lambda n_k, rp_k, ci_k, va_k: h.spmm(N, M, rp_k, ci_k, va_k, B, C, F, dt=dt, workspace=ws, stream=stream)
+            sddmm = lambda n_k, rp_k, ci_k, va_k: h.sddmm(N, M, rp_k, ci_k, X, B, out, F, dt=dt, workspace=ws, stream=stream, nnz=n_k)
+            for name, fn, left_out in (("SpMM", spmm, "adding S partial rows of C"), ("SDDMM", sddmm, "nothing")):
+                if name == "SDDMM" and args.no_sddmm:
+                    continue
+                t_full = timed(lambda: fn(nnz, rp, ci, va), args.iters)
+                t_cut = timed(lambda: [fn(*part) for part in parts], args.iters)
+                print("| %s | %d | %d | %.0f | %.3f | %.3f | %.2f | %s |" % (name, F, S, M * F * esz / S / 1e6, t_full, t_cut,
+                                                                       t_cut / t_full, left_out), flush=True)
+            del B, X, C, out, ws
+        h.close()
+        return
 
     if args.attention:
         if N != M:
