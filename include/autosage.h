@@ -106,7 +106,11 @@ typedef struct {
  * AUTOSAGE_ALPHA, AUTOSAGE_CACHE (file loaded now and saved by autosage_destroy),
  * AUTOSAGE_REPLAY_ONLY); the paper's Implementation section names them.
  * device_id < 0 creates a host-only handle: selector, cache and estimate functions work,
- * every compute call returns AUTOSAGE_ERR_UNSUPPORTED. */
+ * every compute call returns AUTOSAGE_ERR_UNSUPPORTED.
+ * Ownership: a device handle holds two small device buffers of its own (8.5 KB for the degree
+ * features the selector reads back, 256 bytes for the index-check flag), a pinned host mirror
+ * and two events, all made here and released by autosage_destroy; no compute call allocates,
+ * and every other byte of device memory a call touches is the caller's. */
 autosage_status_t autosage_create(autosage_handle_t* out, int device_id);
 autosage_status_t autosage_destroy(autosage_handle_t h);
 const char* autosage_status_string(autosage_status_t s);
