@@ -3,6 +3,8 @@
 // library's device image instead of a caller-provided workspace.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "internal.h"
 
 namespace {
@@ -13,6 +15,7 @@ static __device__ __align__(256) unsigned char scratch[AUTOSAGE_STATIC_SCRATCH_B
 
 constexpr int kMaxDevices = 64;
 void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;     // handles may be created from several threads
 
 }  // namespace
 
@@ -21,6 +24,7 @@ namespace autosage {
 autosage_status_t static_scratch_address(int device, void** ptr)
 {
     if (!ptr || device < 0 || device >= kMaxDevices) return AUTOSAGE_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
     if (!g_scratch_ptr[device]) {
         void* p = nullptr;
         if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return AUTOSAGE_ERR_HIP;
