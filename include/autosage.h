@@ -323,8 +323,9 @@ autosage_status_t autosage_csr_row_softmax_backward(autosage_handle_t h, int64_t
  * row of A^T the entries are in ascending source-row order (storage order for duplicates), so the result
  * is unique.  perm[nnz] (dev, may be NULL) receives the position in A of every entry of A^T; t_val[nnz]
  * (dev) = val[perm] (both NULL for a pattern-only transpose).  Integer outputs are bit-reproducible.
- * The workspace size comes from autosage_csr_transpose_workspace_bytes (needs a device handle: the
- * sort primitive sizes its scratch for the device).  Enqueues only; no synchronisation. */
+ * The workspace size comes from autosage_csr_transpose_workspace_bytes (three index buffers of nnz
+ * entries, a fourth for the sort, and nnz / 16 counters; needs a device handle).  Enqueues only; no
+ * synchronisation. */
 autosage_status_t autosage_csr_transpose_workspace_bytes(autosage_handle_t h, int64_t n_rows, int64_t n_cols,
                                                          int64_t nnz, size_t* bytes);
 autosage_status_t autosage_csr_transpose(autosage_handle_t h, int64_t n_rows, int64_t n_cols, int64_t nnz,

@@ -1284,14 +1284,14 @@ static size_t transpose_workspace(int64_t nnz, int64_t n_cols, size_t* temp_byte
     const size_t ints = align_up(sizeof(int32_t) * (size_t)(nnz > 0 ? nnz : 1), 256);
     const size_t temp = align_up(transpose_sort_temp_bytes(nnz > 0 ? nnz : 1, n_cols), 256);
     if (temp_bytes) *temp_bytes = temp;
-    return 3 * ints + temp;                 // sorted keys, iota, permutation (when the caller keeps none), sort scratch
+    return 3 * ints + temp;                 // two key buffers, permutation (when the caller keeps none), sort scratch
 }
 
 extern "C" autosage_status_t autosage_csr_transpose_workspace_bytes(autosage_handle_t h, int64_t n_rows, int64_t n_cols,
                                                                     int64_t nnz, size_t* bytes)
 {
     if (!h || !bytes || !sizes_ok(n_rows, n_cols, nnz)) return AUTOSAGE_ERR_INVALID_ARG;
-    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;          // the sort primitive sizes its scratch for the device
+    if (h->device < 0) return AUTOSAGE_ERR_UNSUPPORTED;
     *bytes = transpose_workspace(nnz, n_cols, nullptr);
     return AUTOSAGE_OK;
 }
@@ -1311,13 +1311,13 @@ extern "C" autosage_status_t autosage_csr_transpose(autosage_handle_t h, int64_t
         return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
     const size_t ints = align_up(sizeof(int32_t) * (size_t)(nnz > 0 ? nnz : 1), 256);
     char* p = static_cast<char*>(workspace);
-    int32_t* keys_out = reinterpret_cast<int32_t*>(p);
-    int32_t* iota = reinterpret_cast<int32_t*>(p + ints);
+    int32_t* keys_a = reinterpret_cast<int32_t*>(p);
+    int32_t* keys_b = reinterpret_cast<int32_t*>(p + ints);
     int32_t* perm_buf = perm ? perm : reinterpret_cast<int32_t*>(p + 2 * ints);
     void* temp = p + 3 * ints;
     hipStream_t st = static_cast<hipStream_t>(stream);
     STAGE(h, "csr_transpose", st,
-          launch_csr_transpose(n_rows, n_cols, nnz, rowptr, colind, val, t_rowptr, t_colind, t_val, perm_buf, keys_out, iota,
+          launch_csr_transpose(n_rows, n_cols, nnz, rowptr, colind, val, t_rowptr, t_colind, t_val, perm_buf, keys_a, keys_b,
                                temp, temp_bytes, st));
     return AUTOSAGE_OK;
 }

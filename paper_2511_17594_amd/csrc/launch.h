@@ -154,11 +154,12 @@ struct SoftmaxBwdArgs {
 hipError_t launch_softmax_bwd(const SoftmaxBwdArgs& a, int32_t hub_t, int32_t hub_chunk, int32_t group, const HubMeta* meta,
                               float* part, hipStream_t stream);
 
-// CSR transpose: stable sort of the nonzeros by column + index kernels.
+// CSR transpose: stable radix sort of the nonzeros by column + index kernels.  keys_a, keys_b: int32[nnz] scratch;
+// temp: transpose_sort_temp_bytes(nnz, n_cols) bytes (second value buffer, digit histograms, scan sums).
 size_t transpose_sort_temp_bytes(int64_t nnz, int64_t n_cols);
 hipError_t launch_csr_transpose(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t* rowptr, const int32_t* colind,
                                 const float* val, int32_t* t_rowptr, int32_t* t_colind, float* t_val, int32_t* perm,
-                                int32_t* keys_out, int32_t* iota, void* temp, size_t temp_bytes, hipStream_t stream);
+                                int32_t* keys_a, int32_t* keys_b, void* temp, size_t temp_bytes, hipStream_t stream);
 // out[q, :] = in[perm[q], :] for rows of `width` floats.
 hipError_t launch_gather_rows(const int32_t* perm, int64_t n, int32_t width, const float* in, float* out, hipStream_t stream);
 

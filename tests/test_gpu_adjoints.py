@@ -48,7 +48,10 @@ def gpu_transpose(torch, handle, A, with_val=True, keep_perm=True):
     return t_rowptr, t_colind, t_val, perm
 
 
-@pytest.mark.parametrize("n_rows,n_cols", [(5003, 5003), (3000, 777), (400, 9001)])
+# column counts that take one, two, three and four 8-bit passes of the sort; nonzero counts from a fraction of a
+# 4096-key tile to dozens of tiles with a ragged last one
+@pytest.mark.parametrize("n_rows,n_cols", [(5003, 5003), (3000, 777), (400, 9001), (900, 200), (30011, 70001),
+                                           (1500, (1 << 24) + 5), (37, 41)])
 def test_transpose_bit_exact(torch, handle, ab, n_rows, n_cols):
     A = skew(n_rows, n_cols, n_rows)
     o_ptr, o_col, o_val, o_perm = oracle.csr_transpose(A.rowptr, A.colind, A.val, A.n_cols)

@@ -323,6 +323,25 @@ def rows_only(A, rows):
     return out_rp.astype(np.int32), np.ascontiguousarray(A.colind[idx])
 
 
+def test_config4_transpose_full_size(torch, handle, config4):
+    """The CSR transpose (three passes of the radix sort over 1.27e8 keys) against the oracle's, every integer."""
+    A, (rp, ci, va) = config4
+    N, nnz = A.n_rows, A.nnz
+    t_rp = torch.full((N + 1,), -1, dtype=torch.int32, device="cuda")
+    t_ci = torch.full((nnz,), -1, dtype=torch.int32, device="cuda")
+    perm = torch.full((nnz,), -1, dtype=torch.int32, device="cuda")
+    t_va = torch.full((nnz,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(handle.csr_transpose_workspace_bytes(N, N, nnz), dtype=torch.uint8, device="cuda")
+    handle.csr_transpose(N, N, nnz, rp, ci, va, t_rp, t_ci, t_va, perm, ws)
+    torch.cuda.synchronize()
+    del ws
+    o_ptr, o_col, o_val, o_perm = oracle.csr_transpose(A.rowptr, A.colind, A.val, N)
+    assert np.array_equal(t_rp.cpu().numpy(), o_ptr)
+    assert np.array_equal(perm.cpu().numpy(), o_perm)
+    assert np.array_equal(t_ci.cpu().numpy(), o_col)
+    assert np.array_equal(t_va.cpu().numpy(), o_val)
+
+
 def test_config5_attention_backward_full_size(torch, ab, handle, config2):
     """Adjoint of the attention of config 5 at full size.  dQ of a row depends on that row only, so sampled rows
     (the 16 longest among them) are compared with the oracle run on the pattern with all other rows emptied; dK
