@@ -51,7 +51,7 @@ def gpu_transpose(torch, handle, A, with_val=True, keep_perm=True):
 # column counts that take one, two, three and four 8-bit passes of the sort; nonzero counts from a fraction of a
 # 4096-key tile to dozens of tiles with a ragged last one
 @pytest.mark.parametrize("n_rows,n_cols", [(5003, 5003), (3000, 777), (400, 9001), (900, 200), (30011, 70001),
-                                           (1500, (1 << 24) + 5), (37, 41)])
+                                           (1500, (1 << 24) + 5), (37, 41), (9000, 1), (20000, 2)])
 def test_transpose_bit_exact(torch, handle, ab, n_rows, n_cols):
     A = skew(n_rows, n_cols, n_rows)
     o_ptr, o_col, o_val, o_perm = oracle.csr_transpose(A.rowptr, A.colind, A.val, A.n_cols)
@@ -69,6 +69,24 @@ def test_transpose_bit_exact(torch, handle, ab, n_rows, n_cols):
     handle.gather_values(A.nnz, 3, perm, vals, outv)
     torch.cuda.synchronize()
     assert torch.equal(outv, vals[perm[:A.nnz].long()])
+
+
+@pytest.mark.parametrize("nnz", [1, 63, 64, 4095, 4096, 4097, 3 * 4096])
+def test_transpose_tile_boundaries_and_equal_keys(torch, handle, ab, nnz):
+    """Nonzero counts around the sort's tile of 4096 keys; one case with a single column (all keys equal), one with
+    every key distinct."""
+    for kind in ("one_column", "distinct"):
+        if kind == "one_column":
+            A = W.CSR(nnz, 1, np.arange(nnz + 1, dtype=np.int32), np.zeros(nnz, np.int32), np.arange(nnz, dtype=np.float32))
+        else:
+            cols = np.random.default_rng(nnz).permutation(nnz).astype(np.int32)
+            A = W.CSR(1, nnz, np.array([0, nnz], np.int32), cols, np.arange(nnz, dtype=np.float32))
+        o_ptr, o_col, o_val, o_perm = oracle.csr_transpose(A.rowptr, A.colind, A.val, A.n_cols)
+        t_rowptr, t_colind, t_val, perm = gpu_transpose(torch, handle, A)
+        assert np.array_equal(t_rowptr.cpu().numpy(), o_ptr), kind
+        assert np.array_equal(t_colind.cpu().numpy()[:nnz], o_col), kind
+        assert np.array_equal(perm.cpu().numpy()[:nnz], o_perm), kind
+        assert np.array_equal(t_val.cpu().numpy()[:nnz], o_val), kind
 
 
 def test_transpose_degenerate(torch, handle, ab):
