@@ -123,6 +123,9 @@ const char* autosage_status_string(autosage_status_t s);
  * Row-softmax (forward and backward): "softmax_group" = lanes that share one light row (rounded up to
  * a power of two <= 64, at least the lanes one entry of H heads takes); 0 (default) derives it from
  * the mean row length, a negative value keeps one wavefront per row.
+ * Attention backward: "attention_backward_fused" (1, default: dQ, P and dS come from one pass over the K and V rows
+ * of every nonzero wherever the single-pass forward kernels cover the head count and width; 0: always the chain rule
+ * stage by stage).
  * Unknown name -> AUTOSAGE_ERR_INVALID_ARG. */
 autosage_status_t autosage_set_param(autosage_handle_t h, const char* name, double value);
 autosage_status_t autosage_get_param(autosage_handle_t h, const char* name, double* value);
@@ -343,13 +346,16 @@ autosage_status_t autosage_gather_values(autosage_handle_t h, int64_t n, int32_t
  *   dV[j,h,:] = sum_p P[p,h] dO[i,h,:],   dP[p,h] = <dO[i,h,:], V[j,h,:]>,   dS = softmax'(P, dP),
  *   dQ[i,h,:] = scale sum_p dS[p,h] K[j,h,:],   dK[j,h,:] = scale sum_p dS[p,h] Q[i,h,:]
  * over the stored p = (i, j); the probabilities P are recomputed from Q and K, not stored by the forward.
+ * Where the single-pass forward kernels cover (H, d, in_dt), dQ, P and dS come from one pass that reads the K and
+ * the V row of every nonzero once (parameter "attention_backward_fused"); dK and dV are per-head-weight SpMMs on
+ * the transposed pattern that read P and dS through perm.
  * Q, K, V: [N, H, d] of in_dt (dev); dO, dQ, dK, dV: [N, H, d] fp32 (dev), none aliasing another.
  * (t_rowptr, t_colind, perm) is the transposed pattern as autosage_csr_transpose returns it for the
  * N x N pattern (computed once per graph by the caller).  hub_t / hub_chunk: rows of the pattern and of
  * its transpose with at least hub_t entries are split into chunks (0 = no split).  Shapes as the forward:
  * d * sizeof(in_dt) a multiple of 16, d a multiple of 4, 16-byte aligned tensors, else UNSUPPORTED.
  * Rows without entries get zero gradients.  Deterministic: no atomics, fixed summation orders.
- * Workspace from autosage_csr_attention_backward_workspace_bytes (3 * nnz * H floats + hub scratch). */
+ * Workspace from autosage_csr_attention_backward_workspace_bytes (2 * nnz * H + 3 * N * H floats + hub scratch). */
 autosage_status_t autosage_csr_attention_backward_workspace_bytes(autosage_handle_t h, int64_t N, int64_t nnz,
                                                                   int32_t H, int32_t d, int32_t hub_t,
                                                                   int32_t hub_chunk, size_t* bytes);
@@ -367,7 +373,8 @@ autosage_status_t autosage_csr_attention_backward(autosage_handle_t h, int64_t N
  * profile_read every kernel stage the handle launches is bracketed by a pair of HIP events on its
  * stream.  profile_read waits for the recorded stages, writes JSON {"stage":{"calls":n,"total_ms":t},...}
  * (stage names: hub_partition, spmm_rows, spmm_hub, sddmm_rows, sddmm_hub, softmax_rows, softmax_hub,
- * attn_sddmm_rows, attn_sddmm_hub, attn_spmm_rows, attn_spmm_hub, attn_fused_rows, attn_fused_hub) and
+ * attn_sddmm_rows, attn_sddmm_hub, attn_spmm_rows, attn_spmm_hub, attn_fused_rows, attn_fused_hub, attn_bwd_rows,
+ * attn_bwd_hub, attn_bwd_finish, attn_bwd_spmm_rows, attn_bwd_spmm_hub, ...) and
  * switches profiling off. */
 autosage_status_t autosage_profile_begin(autosage_handle_t h);
 autosage_status_t autosage_profile_read(autosage_handle_t h, char* json_buf, size_t n);

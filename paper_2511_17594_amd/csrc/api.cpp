@@ -468,6 +468,7 @@ static bool param_access(Params& p, const char* name, double* value, bool set)
     P_INT("force_wpb", force_wpb)
     P_INT("force_hub_t", force_hub_t)
     P_INT("softmax_group", softmax_group)
+    P_INT("attention_backward_fused", attention_backward_fused)
 #undef P_DOUBLE
 #undef P_INT
     return false;
@@ -893,21 +894,36 @@ extern "C" autosage_status_t autosage_workspace_bytes(autosage_handle_t h, autos
 }
 
 // ------------------------------------------------------------------------------------------
-// attention backward: the chain rule through the three stages, all heads at once
+// attention backward: the chain rule through the three stages, all heads at once; the half on the pattern itself in
+// one pass over K and V where the single-pass kernels cover the shape
 // ------------------------------------------------------------------------------------------
 namespace autosage {
 
-// Workspace: P [nnz, H] | D [nnz, H] (dP, then dS) | T [nnz, H] (weights in the order of A^T) | hub partition
-// + partial buffer (partitioned for A first, for A^T afterwards).
+// Workspace: P [nnz, H] | D [nnz, H] (dP, then dS) | per-row records [N, H, 3] of the single pass | hub partition
+// + partial buffer (partitioned for A first, for A^T afterwards).  The transposed side reads P and dS through the
+// permutation, so no copy in the order of A^T is kept.
+// Floats of partial state per hub chunk: the stage-by-stage kernels and, over the element types (the type is not an
+// argument of the size query), the single pass over K and V.
+static size_t attention_bwd_part_floats(int32_t H, int32_t d)
+{
+    size_t f = attention_part_floats(H, d);
+    AttnShape sh{};
+    for (int dt = DT_F32; dt <= DT_F16; ++dt)
+        if (attn_fused_shape(H, d, dt, &sh)) f = std::max(f, attn_bwd_part_floats(sh));
+    return f;
+}
+
 static size_t attention_bwd_hub_bytes(int64_t N, int64_t nnz, int32_t H, int32_t d, int hub_t, int chunk)
 {
-    return hub_workspace_bytes(N, nnz, hub_t, chunk, (int64_t)attention_part_floats(H, d));
+    return hub_workspace_bytes(N, nnz, hub_t, chunk, (int64_t)attention_bwd_part_floats(H, d));
 }
+
+static size_t attention_bwd_stats_bytes(int64_t N, int32_t H) { return align_up(sizeof(float) * 3 * (size_t)(N > 0 ? N : 1) * H, 256); }
 
 static size_t attention_bwd_bytes(int64_t N, int64_t nnz, int32_t H, int32_t d, int hub_t, int chunk)
 {
     const size_t cells = align_up(sizeof(float) * (size_t)(nnz > 0 ? nnz : 1) * H, 256);
-    return 3 * cells + attention_bwd_hub_bytes(N, nnz, H, d, hub_t, chunk);
+    return 2 * cells + attention_bwd_stats_bytes(N, H) + attention_bwd_hub_bytes(N, nnz, H, d, hub_t, chunk);
 }
 
 struct AttnBwdCall {
@@ -947,15 +963,16 @@ static autosage_status_t exec_attention_backward(autosage_ctx* h, const AttnBwdC
     char* base = static_cast<char*>(workspace);
     float* P = reinterpret_cast<float*>(base);
     float* D = reinterpret_cast<float*>(base + cells);
-    float* T = reinterpret_cast<float*>(base + 2 * cells);
-    void* hub_ws = base + 3 * cells;
-    const size_t hub_ws_bytes = workspace_bytes - 3 * cells;
+    float* stats = reinterpret_cast<float*>(base + 2 * cells);
+    const size_t head = 2 * cells + attention_bwd_stats_bytes(N, H);
+    void* hub_ws = base + head;
+    const size_t hub_ws_bytes = workspace_bytes - head;
 
     HubMeta meta{};
     float* part = nullptr;
     auto partition = [&](const int32_t* rowptr) -> autosage_status_t {
         if (rs.hub_t <= 0) return AUTOSAGE_OK;
-        if (!carve_hub(hub_ws, hub_ws_bytes, N, nnz, rs.hub_t, rs.hub_chunk, (int64_t)attention_part_floats(H, d), &meta, &part,
+        if (!carve_hub(hub_ws, hub_ws_bytes, N, nnz, rs.hub_t, rs.hub_chunk, (int64_t)attention_bwd_part_floats(H, d), &meta, &part,
                        nullptr))
             return AUTOSAGE_ERR_WORKSPACE_TOO_SMALL;
         STAGE(h, "hub_partition", st, launch_hub_partition(rows, rowptr, rs.hub_t, rs.hub_chunk, meta, st));
@@ -980,13 +997,14 @@ static autosage_status_t exec_attention_backward(autosage_ctx* h, const AttnBwdC
         if (rs.hub_t > 0) STAGE(h, "attn_bwd_sddmm_hub", st, launch_sddmm_hub(a, rs, meta, st));
         return AUTOSAGE_OK;
     };
-    auto spmm = [&](const int32_t* rowptr, const int32_t* colind, const float* w, const void* B, int dt, const Resolved& r,
-                    float* out) -> autosage_status_t {
+    auto spmm = [&](const int32_t* rowptr, const int32_t* colind, const float* w, const int32_t* w_at, const void* B, int dt,
+                    const Resolved& r, float* out) -> autosage_status_t {
         SpmmArgs a{};
         a.rows = rows;
         a.rowptr = rowptr;
         a.colind = colind;
         a.val = w;
+        a.val_index = w_at;
         a.B = B;
         a.ldb = HD;
         a.C = out;
@@ -1003,7 +1021,35 @@ static autosage_status_t exec_attention_backward(autosage_ctx* h, const AttnBwdC
     // forward pattern: P = softmax(scale * Q K^T), dP = <dO, V>, dS = scale * softmax'(P, dP), dQ = dS K
     rc = partition(c.rowptr);
     if (rc != AUTOSAGE_OK) return rc;
-    if (nnz > 0) {
+    AttnShape shape{};
+    const bool one_pass = h->params.attention_backward_fused != 0 && attn_fused_shape(H, d, c.dt, &shape);
+    if (one_pass) {
+        // one walk over K and V per row: dQ, and P and dS left in the two [nnz, H] arrays
+        shape.wpg = rs.wpg;
+        shape.hub_t = rs.hub_t;
+        shape.hub_chunk = rs.hub_chunk;
+        shape.heads_tile = H;
+        shape.tiles = 1;
+        AttnBwdArgs fa{};
+        fa.rows = rows;
+        fa.rowptr = c.rowptr;
+        fa.colind = c.colind;
+        fa.Q = c.Q;
+        fa.K = c.K;
+        fa.V = c.V;
+        fa.dO = c.dO;
+        fa.dQ = c.dQ;
+        fa.S = P;
+        fa.D = D;
+        fa.stats = stats;
+        fa.H = H;
+        fa.d = d;
+        fa.dt = c.dt;
+        fa.scale = c.scale;
+        STAGE(h, "attn_bwd_rows", st, launch_attn_bwd_rows(fa, shape, st));
+        if (rs.hub_t > 0) STAGE(h, "attn_bwd_hub", st, launch_attn_bwd_hub(fa, shape, meta, part, st));
+        if (nnz > 0) STAGE(h, "attn_bwd_finish", st, launch_attn_bwd_finish(fa, shape, rs.hub_t > 0 ? &meta : nullptr, st));
+    } else if (nnz > 0) {
         rc = sddmm(c.Q, false, c.K, c.scale, P);
         if (rc != AUTOSAGE_OK) return rc;
         SoftmaxArgs ma{};
@@ -1027,17 +1073,18 @@ static autosage_status_t exec_attention_backward(autosage_ctx* h, const AttnBwdC
         STAGE(h, "attn_bwd_softmax", st, launch_softmax_bwd(ba, rs.hub_t, rs.hub_chunk, softmax_group(h, ba.rows.count, nnz, ba.H),
                                                                 rs.hub_t > 0 ? &meta : nullptr, part, st));
     }
-    rc = spmm(c.rowptr, c.colind, D, c.K, c.dt, rp, c.dQ);
-    if (rc != AUTOSAGE_OK) return rc;
+    if (!one_pass) {
+        rc = spmm(c.rowptr, c.colind, D, nullptr, c.K, c.dt, rp, c.dQ);
+        if (rc != AUTOSAGE_OK) return rc;
+    }
 
     // transposed pattern: dV = P^T dO, dK = dS^T Q
     rc = partition(c.t_rowptr);
     if (rc != AUTOSAGE_OK) return rc;
-    if (nnz > 0) STAGE(h, "gather_values", st, launch_gather_rows(c.perm, nnz, H, P, T, st));
-    rc = spmm(c.t_rowptr, c.t_colind, T, c.dO, DT_F32, rp32, c.dV);
+    // the weights of an entry of the transposed pattern sit at its source position: read through the permutation
+    rc = spmm(c.t_rowptr, c.t_colind, P, c.perm, c.dO, DT_F32, rp32, c.dV);
     if (rc != AUTOSAGE_OK) return rc;
-    if (nnz > 0) STAGE(h, "gather_values", st, launch_gather_rows(c.perm, nnz, H, D, T, st));
-    return spmm(c.t_rowptr, c.t_colind, T, c.Q, c.dt, rp, c.dK);
+    return spmm(c.t_rowptr, c.t_colind, D, c.perm, c.Q, c.dt, rp, c.dK);
 }
 
 }  // namespace autosage

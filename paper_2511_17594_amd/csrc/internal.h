@@ -73,6 +73,9 @@ struct Params {
     int force_hub_t = -1;     // -1 = not forced, 0 = forced off
     // row-softmax: lanes per light row (0 = from the mean row length, < 0 = one wavefront per row)
     int softmax_group = 0;
+    // attention backward: 1 = dQ, P and dS from one pass over K and V where the single-pass kernels cover the shape,
+    // 0 = always the chain rule stage by stage
+    int attention_backward_fused = 1;
 };
 
 }  // namespace autosage

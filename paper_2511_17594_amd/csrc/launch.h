@@ -66,6 +66,7 @@ struct SpmmArgs {
     const int32_t* rowptr;
     const int32_t* colind;
     const float* val;      // [nnz] (heads == 1) or [nnz, heads] per-head weights
+    const int32_t* val_index;  // nullptr, or [nnz]: nonzero p takes the weights at val_index[p] (wavefront-per-row mapping only)
     const void* B;         // [n_cols, F] (heads == 1) or [n_cols, heads, d] with F = heads * d
     int64_t ldb;
     float* C;
@@ -138,6 +139,33 @@ bool attn_fused_shape_tiled(int32_t H, int32_t d, int dt, int32_t heads_tile, At
 size_t attn_fused_part_floats(const AttnShape& s);
 hipError_t launch_attn_fused_rows(const AttnArgs& a, const AttnShape& s, hipStream_t stream);
 hipError_t launch_attn_fused_hub(const AttnArgs& a, const AttnShape& s, const HubMeta& meta, float* part, hipStream_t stream);
+
+// Backward of the attention on the pattern itself, single pass (see attention_kernels.inc): dQ, the scores' gradient
+// and the probabilities for the transposed side.
+struct AttnBwdArgs {
+    RowMap rows;
+    const int32_t* rowptr;
+    const int32_t* colind;
+    const void* Q;         // [n_rows, H, d]
+    const void* K;         // [n_cols, H, d]
+    const void* V;         // [n_cols, H, d]
+    const float* dO;       // [n_rows, H, d]
+    float* dQ;             // [n_rows, H, d]
+    float* S;              // [nnz, H] out: P
+    float* D;              // [nnz, H] out: dS (scale included)
+    float* stats;          // [n_rows, H, 3] scratch: m, 1 / l, delta per row and head
+    int32_t H;
+    int32_t d;
+    int32_t dt;
+    float scale;
+};
+// Floats of partial state per hub chunk of the backward pass.
+size_t attn_bwd_part_floats(const AttnShape& s);
+// Light rows / hub rows of the pass (raw scores and dP in S and D, per-row records in stats) ...
+hipError_t launch_attn_bwd_rows(const AttnBwdArgs& a, const AttnShape& s, hipStream_t stream);
+hipError_t launch_attn_bwd_hub(const AttnBwdArgs& a, const AttnShape& s, const HubMeta& meta, float* part, hipStream_t stream);
+// ... and the streaming kernels that turn S and D into P and dS (meta: nullptr without a hub split).
+hipError_t launch_attn_bwd_finish(const AttnBwdArgs& a, const AttnShape& s, const HubMeta* meta, hipStream_t stream);
 
 struct SoftmaxBwdArgs {
     RowMap rows;

@@ -11,7 +11,7 @@ algorithm and its SDDMM, called directly through `vendor.py`).
 `--attention` prints the CSR-attention table instead (H = 8, d = 64, 16-bit operands from `--dtype`, default
 bf16): the selector's choice, the single pass and the three-stage pipeline at fixed split thresholds, and
 the backward call; bytes are the algorithmic ones (a K and a V row per nonzero, plus 16 bytes per score and
-head for the three stages).  `--softmax` prints the row-softmax table instead (forward and backward, H = 1 and 8, over split
+head for the three stages; backward: K, V, Q rows and an fp32 dO row per nonzero, 32 bytes per score and head).  `--softmax` prints the row-softmax table instead (forward and backward, H = 1 and 8, over split
 thresholds): 8 bytes per score forward (read + write), 12 backward (P, dP read, dS written).
 Workloads: config1..4 (the benchmark configurations), er (Erdos-Renyi N = 200000, p = 2e-5, the shape of
 the paper's extreme-sparsity stressor) and hubsplit_5k / hubsplit_12k (N = 20000, a few rows of degree
@@ -238,8 +238,9 @@ def main(argv=None):
         wsb = torch.empty(h.csr_attention_backward_workspace_bytes(N, nnz, H, d, hub_b), dtype=torch.uint8, device="cuda")
         tb = timed(lambda: h.csr_attention_backward(N, rp, ci, t_rp, t_ci, perm, Q, K, V, dO, dQ, dK, dV, H, d, scale, in_dt=in_dt,
                                                     hub_t=hub_b, workspace=wsb, stream=stream, nnz=nnz), max(3, args.iters // 2))
-        # gathered rows: K twice and V once (16-bit), Q once (16-bit), dO once (fp32); scores: about 14 passes of [nnz, H] fp32
-        b_bwd = nnz * HD * (4.0 * e + 4.0) + 14.0 * 4 * nnz * H + 5.0 * N * HD * 4
+        # gathered rows: K and V once (16-bit, one pass for dQ, P and dS), Q once (16-bit) and dO once (fp32) on the
+        # transposed side; scores: 8 passes of [nnz, H] fp32 (s and dP written, read, P and dS written and read once more)
+        b_bwd = nnz * HD * (3.0 * e + 4.0) + 8.0 * 4 * nnz * H + 4.0 * nnz + 5.0 * N * HD * 4
         print("| backward | %d | %.3f | %.0f | %.2f | %.0f | %.0f %% |" % (hub_b, tb, 10.0 * nnz * HD / tb / 1e6, b_bwd / 1e9, b_bwd / tb / 1e6,
                                                                       100 * b_bwd / tb / 1e6 / HBM_PEAK_GBS), flush=True)
         h.close()

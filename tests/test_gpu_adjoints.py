@@ -176,9 +176,11 @@ def gradient_term_magnitudes(A, Q, K, V, dO, scale):
     (8, 64, "bf16", 256, 1.0), (8, 64, "bf16", 0, None), (2, 32, "f16", 128, 2.0), (1, 128, "bf16", 64, 1.0),
     (4, 16, "f32", 256, 1.0), (3, 16, "bf16", 512, 1.0), (8, 64, "f32", 0, 1.0),
 ])
-def test_attention_backward(torch, handle, ab, H, d, dtype, hub_t, qk_std):
+@pytest.mark.parametrize("one_pass", [1, 0])
+def test_attention_backward(torch, handle, ab, H, d, dtype, hub_t, qk_std, one_pass):
     """dQ, dK, dV of the library against the oracle's chain rule, on a skewed square pattern with hub rows in
-    the pattern and in its transpose, empty rows, and columns nobody attends to."""
+    the pattern and in its transpose, empty rows, and columns nobody attends to; with the pattern-side half taken
+    in one pass over K and V (where the shape has such kernels) and stage by stage."""
     from util import dtype_code
     n = 3001
     A = skew(n, n - 40, seed=900 + H + d)
@@ -200,11 +202,13 @@ def test_attention_backward(torch, handle, ab, H, d, dtype, hub_t, qk_std):
     t_rowptr, t_colind, _, perm = gpu_transpose(torch, handle, A, with_val=False)
     outs = [torch.full((n, H, d), float("nan"), dtype=torch.float32, device="cuda") for _ in range(3)]
     ws = torch.empty(handle.csr_attention_backward_workspace_bytes(n, A.nnz, H, d, hub_t), dtype=torch.uint8, device="cuda")
-    print("attention backward H %d d %d %s hub %d" % (H, d, dtype, hub_t), flush=True)
+    print("attention backward H %d d %d %s hub %d one pass %d" % (H, d, dtype, hub_t, one_pass), flush=True)
+    handle.set_param("attention_backward_fused", one_pass)
     handle.csr_attention_backward(n, dev(A.rowptr, torch), dev(A.colind, torch), t_rowptr, t_colind, perm,
                                   dev(Q, torch), dev(K, torch), dev(V, torch), dev(dO, torch), *outs, H, d, scale,
                                   in_dt=dtype_code(ab, Q), hub_t=hub_t, workspace=ws, nnz=A.nnz)
     torch.cuda.synchronize()
+    handle.set_param("attention_backward_fused", 1)
     unused = np.setdiff1d(np.arange(n), A.colind)
     assert unused.size > 0
     for name, got_t, want, mag in zip(("dQ", "dK", "dV"), outs, ref, ref_abs):
