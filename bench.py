@@ -363,6 +363,31 @@ def main():
                    {k: round(v, 3) for k, v in detail["hipsparse_spmm_dense_community_F128_ms"].items()}))
         except Exception as e:                # pragma: no cover
             log("hipSPARSE unavailable: %r" % (e,))
+        # adjoints a training step adds (reported beside the step, not part of it): CSR transpose of the large sparse
+        # pattern, and the attention backward on the power-law pattern
+        adj = {}
+        t_rp = torch.empty(w4.N + 1, dtype=torch.int32, device="cuda")
+        t_ci = torch.empty(w4.nnz, dtype=torch.int32, device="cuda")
+        perm = torch.empty(w4.nnz, dtype=torch.int32, device="cuda")
+        wst = torch.empty(w4.h.csr_transpose_workspace_bytes(w4.N, w4.N, w4.nnz), dtype=torch.uint8, device="cuda")
+        adj["transpose_large_sparse_ms"] = timed(lambda: w4.h.csr_transpose(w4.N, w4.N, w4.nnz, w4.rp, w4.ci, None, t_rp, t_ci, None,
+                                                                           perm, wst, stream=stream), iters=3)
+        del t_rp, t_ci, perm, wst
+        t_rp = torch.empty(w5.N + 1, dtype=torch.int32, device="cuda")
+        t_ci = torch.empty(w5.nnz, dtype=torch.int32, device="cuda")
+        perm = torch.empty(w5.nnz, dtype=torch.int32, device="cuda")
+        wst = torch.empty(w5.h.csr_transpose_workspace_bytes(w5.N, w5.N, w5.nnz), dtype=torch.uint8, device="cuda")
+        w5.h.csr_transpose(w5.N, w5.N, w5.nnz, w5.rp, w5.ci, None, t_rp, t_ci, None, perm, wst, stream=stream)
+        del wst
+        dO = torch.randn((w5.N, H, d), device="cuda")
+        dQ, dK, dV = (torch.empty((w5.N, H, d), device="cuda") for _ in range(3))
+        wsb = torch.empty(w5.h.csr_attention_backward_workspace_bytes(w5.N, w5.nnz, H, d, 512), dtype=torch.uint8, device="cuda")
+        adj["attention_backward_power_law_ms"] = timed(
+            lambda: w5.h.csr_attention_backward(w5.N, w5.rp, w5.ci, t_rp, t_ci, perm, w5.Q, w5.K, w5.V, dO, dQ, dK, dV, H, d, scale,
+                                                in_dt=ab.BF16, hub_t=512, workspace=wsb, stream=stream, nnz=w5.nnz), iters=5)
+        del t_rp, t_ci, perm, dO, dQ, dK, dV, wsb
+        detail["adjoints"] = adj
+        log("adjoints: %s" % {k: round(v, 3) for k, v in adj.items()})
         # the guardrail's fallback kernel on the step's own calls (one run each: it walks a 541 482-long row on one wavefront)
         fb = {}
         fb["large_sparse.spmm"] = timed(lambda: w4.h.spmm(w4.N, w4.N, w4.rp, w4.ci, w4.va, w4.B, w4.C, F, sched=base, workspace=ws, stream=stream), iters=1)
