@@ -119,6 +119,7 @@ constexpr int kBaselineBoundDeg = 1024;     // rows this long are left out when 
 constexpr int kSelectorMinHubT = 512;      // smallest threshold the selector proposes for SpMM / SDDMM
 constexpr int kSelectorMinChunk = 256;     // shortest hub chunk the selector proposes
 constexpr double kRefineGain = 0.97;        // a refinement probe must take at most this share of the best time so far to count
+constexpr double kFullInputCapMs = 1.0;     // full-input confirmation: timed runs stop once this is spent; a warm-up of 4x this is the measurement
 constexpr double kTileOperandBytes = 96.0 * 1024 * 1024;
 constexpr double kHeadTileOperandBytes = 256.0 * 1024 * 1024;   // K + V above this: the single-pass attention is also tried with head tiles   // dense operands above this get narrow-tile candidates
 

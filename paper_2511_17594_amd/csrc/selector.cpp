@@ -822,9 +822,9 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
     // 6. the guardrail speaks about the sample; confirm once on the whole input
     if (choice >= 0 && h->params.confirm_full) {
         const RowMap full{0, 1, (int32_t)n_rows, 0};
-        // its kernels have run on the sample: up to two timed runs after a warm-up, fewer once 2.5 ms are spent,
-        // and a warm-up of 10 ms or more is itself the measurement (large inputs: one run)
-        double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, 2.5, nullptr, false);
+        // its kernels have run on the sample: up to two timed runs after a warm-up, fewer once kFullInputCapMs are
+        // spent, and a warm-up of four times that or more is itself the measurement (large inputs: one run)
+        double tf_c = time_schedule(h, in, full, cands[choice], workspace, workspace_bytes, st, 2, kFullInputCapMs, nullptr, false);
         // A schedule found by the refinement rounds won on the sample, where a launch is short and latency counts
         // for more than on the whole input.  It is run off against the best of the ranked candidates on the whole
         // input (when that one passes the guardrail too) and the faster of the two is kept.
@@ -838,7 +838,7 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
                 if (c == choice || cands[c].f_tile == cands[choice].f_tile || std::memcmp(&twin, &cands[choice], sizeof twin) != 0)
                     continue;
                 if (!(tc[c] <= h->params.alpha * tb)) break;
-                const double tf_t = time_schedule(h, in, full, cands[c], workspace, workspace_bytes, st, 2, 2.5, nullptr, false);
+                const double tf_t = time_schedule(h, in, full, cands[c], workspace, workspace_bytes, st, 2, kFullInputCapMs, nullptr, false);
                 const bool to_tiled = cands[c].f_tile != 0;
                 const bool switched = to_tiled ? tf_t <= kRefineGain * tf_c : tf_t < tf_c;
                 runoff = ",\"runoff\":{\"index\":" + std::to_string(c) + ",\"t_ms\":" + num(tf_t) + ",\"t_refined_ms\":" +
@@ -856,7 +856,7 @@ static autosage_status_t decide_impl(autosage_handle_t h, const OpInput& in, voi
             for (int c = 0; c < topk; ++c)
                 if (std::isfinite(tc[c]) && (best0 < 0 || tc[c] < tc[best0])) best0 = c;
             if (best0 >= 0 && tc[best0] <= h->params.alpha * tb) {
-                const double tf_0 = time_schedule(h, in, full, cands[best0], workspace, workspace_bytes, st, 2, 2.5, nullptr, false);
+                const double tf_0 = time_schedule(h, in, full, cands[best0], workspace, workspace_bytes, st, 2, kFullInputCapMs, nullptr, false);
                 const bool switched = tf_0 < tf_c;
                 runoff = ",\"runoff\":{\"index\":" + std::to_string(best0) + ",\"t_ms\":" + num(tf_0) + ",\"t_refined_ms\":" +
                          num(tf_c) + ",\"switched\":" + (switched ? "true" : "false") + "}";
