@@ -17,6 +17,7 @@ Workloads: config1..4 (the benchmark configurations), er (Erdos-Renyi N = 200000
 the paper's extreme-sparsity stressor) and hubsplit_5k / hubsplit_12k (N = 20000, a few rows of degree
 5000 / 12000, the rest 64 / 32: the shape of the paper's split-versus-baseline table; the number of hub
 rows is not given there, 32 is used).
+`--transpose` times the CSR transpose of the pattern (pattern only, permutation kept).
 `--column-slices S` measures what processing the pattern in S column ranges would cost, with the library's own
 kernels: the pattern is cut on the host into S patterns that hold the nonzeros of one column range each (so the
 slice of the gathered operand a launch touches is 1/S of it and can stay in the Infinity Cache), every slice is
@@ -76,6 +77,7 @@ def main(argv=None):
     ap.add_argument("--no-fallback", action="store_true", help="do not time the guardrail's fallback kernel")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 1 GiB device-to-device copy three times (known traffic for profiler counter scaling)")
+    ap.add_argument("--transpose", action="store_true", help="time the CSR transpose of the pattern (sort passes, index kernels)")
     ap.add_argument("--column-slices", type=int, default=0,
                     help="time the pattern cut into this many column ranges, one launch per range, beside the unsliced call")
     args = ap.parse_args(argv)
@@ -138,6 +140,19 @@ def main(argv=None):
             out.append((int(keep.sum()), torch.from_numpy(rp_k.astype(np.int32)).cuda(), torch.from_numpy(A.colind[keep]).cuda(),
                         torch.from_numpy(A.val[keep]).cuda()))
         return out
+
+    if args.transpose:
+        t_rp = torch.empty(M + 1, dtype=torch.int32, device="cuda")
+        t_ci = torch.empty(max(nnz, 1), dtype=torch.int32, device="cuda")
+        perm = torch.empty(max(nnz, 1), dtype=torch.int32, device="cuda")
+        wst = torch.empty(h.csr_transpose_workspace_bytes(N, M, nnz), dtype=torch.uint8, device="cuda")
+        t = timed(lambda: h.csr_transpose(N, M, nnz, rp, ci, None, t_rp, t_ci, None, perm, wst, stream=stream), args.iters)
+        passes = (max(1, int(M - 1).bit_length()) + 7) // 8
+        print("| workload | nnz | columns | 8-bit passes | ms | 10^9 keys/s | workspace MB |")
+        print("|---|---|---|---|---|---|---|")
+        print("| %s | %d | %d | %d | %.3f | %.2f | %.0f |" % (args.workload, nnz, M, passes, t, nnz / t / 1e6, wst.numel() / 1e6), flush=True)
+        h.close()
+        return
 
     if args.column_slices > 1:
         S = args.column_slices
