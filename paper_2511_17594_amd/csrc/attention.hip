@@ -112,6 +112,18 @@ struct FinishDev {
 __device__ __forceinline__ void finish_span(const FinishDev& a, int row, int64_t e0, int64_t e1, int first, int stride)
 {
     const float* __restrict__ rec = a.stats + (int64_t)row * a.H * 3;
+    if (stride % a.H == 0) {
+        // e0 is a multiple of H, so a lane stays on one head: its record is read once
+        const int h = first % a.H;
+        const float m = rec[h * 3], inv = rec[h * 3 + 1], delta = rec[h * 3 + 2];
+        for (int64_t e = e0 + first; e < e1; e += stride) {
+            const float p = __expf(a.S[e] - m) * inv;
+            const float dp = a.D[e];
+            a.S[e] = p;
+            a.D[e] = a.scale * p * (dp - delta);
+        }
+        return;
+    }
     for (int64_t e = e0 + first; e < e1; e += stride) {
         const int h = (int)(e % a.H);
         const float p = __expf(a.S[e] - rec[h * 3]) * rec[h * 3 + 1];
